@@ -1,0 +1,153 @@
+/*
+ * memo.h -- C ABI of libmemo, the MI355X (gfx950) hot path of Memo
+ * (arXiv 2407.12117): exact causal attention forward/backward and the
+ * token-wise swap of saved activations.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers unless the name says "host".
+ *     The caller owns every buffer; the library never frees or keeps a pointer
+ *     after the call returns, but work queued on a stream may still read or
+ *     write the buffers until that stream (or the done event) completes.
+ *   - Streams and events are hipStream_t / hipEvent_t passed as void*
+ *     (NULL stream = the default stream).
+ *   - Argument errors are found on the host before anything is queued and are
+ *     reported through the return value; nothing is thrown, nothing is printed.
+ *     A failing HIP call gives MEMO_ERR_DEVICE.  Faults inside a kernel surface
+ *     at the caller's next synchronisation, as with any HIP launch.
+ *   - Calls are asynchronous with respect to the host.
+ */
+#ifndef MEMO_H
+#define MEMO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MEMO_OK = 0,
+    MEMO_ERR_INVALID_ARG = 1,   /* null pointer, bad size, alpha outside [0,1], ... */
+    MEMO_ERR_UNSUPPORTED = 2,   /* head dim / dtype / stride combination not built */
+    MEMO_ERR_HOST_CAPACITY = 3, /* host store smaller than the swapped bytes: the paper's
+                                   host out-of-memory case (Section 4.1, second constraint) */
+    MEMO_ERR_WORKSPACE = 4,     /* workspace missing or smaller than the query says */
+    MEMO_ERR_DEVICE = 5         /* a HIP runtime call failed */
+} memo_status;
+
+typedef enum { MEMO_F32 = 0, MEMO_BF16 = 1 } memo_dtype;
+
+/*
+ * Problem statement of one attention call (Section 2.1.3: Q, K, V of shape
+ * (b, s, h), O = softmax(Q K^T / sqrt(d)) V under the decoder's causal mask).
+ * h is split into H heads of width d; element (b, s, h, c) of every tensor
+ * lives at  b*stride_b + s*stride_s + h*stride_h + c  (strides in elements,
+ * c contiguous).  The token-major layout [B,S,H,d] is stride_b = S*H*d,
+ * stride_s = H*d, stride_h = d.  All of q, k, v, o, d_o, dq, dk, dv share
+ * the strides.  lse and the like are [B,H,S] contiguous fp32.
+ * Supported: MEMO_BF16 with d = 128 (fp32 accumulation, MFMA path);
+ *            MEMO_F32 with d in {64, 128} (fp32 throughout).
+ * S may be any positive length (ragged last tile is handled); causal must be 1.
+ * Rows must be 16-byte aligned: base pointers 16-byte aligned and strides a
+ * multiple of 8 (bf16) or 4 (fp32) elements.
+ */
+typedef struct {
+    int32_t B, H, d;
+    int64_t S;
+    int32_t dtype;              /* memo_dtype */
+    float scale;                /* the 1/sqrt(d) of the formula, passed explicitly */
+    int64_t stride_b, stride_s, stride_h;
+    int32_t causal;             /* must be 1: mask is inclusive, key j visible to query i iff j <= i */
+    uint32_t flags;             /* reserved, must be 0 */
+} memo_attn_desc;
+
+/*
+ * Forward (Section 2.1.3, FlashAttention: tiled, keeps only per-row state).
+ *   o   [same layout as q]  = softmax(scale * q k^T, causal) v
+ *   lse [B,H,S] fp32        = natural-log sum_j exp(scale * q_i . k_j), j <= i
+ * Queued on `stream`.  Returns MEMO_OK or an error; on error nothing is queued.
+ */
+memo_status memo_attn_fwd(const memo_attn_desc *desc, const void *q, const void *k, const void *v,
+                          void *o, float *lse, void *stream);
+
+/*
+ * Backward (Section 2.1.3: the intermediates are re-formed tile by tile).
+ * Given d_o = dL/dO, writes dq, dk, dv (same layout and dtype as q).
+ * Needs o and lse from the forward.  `workspace` is device memory of at least
+ * memo_attn_bwd_workspace_bytes(desc) bytes, 256-byte aligned, owned by the
+ * caller, contents undefined on entry and exit.  Deterministic: no atomics.
+ */
+size_t memo_attn_bwd_workspace_bytes(const memo_attn_desc *desc);
+memo_status memo_attn_bwd(const memo_attn_desc *desc, const void *q, const void *k, const void *v,
+                          const void *o, const float *lse, const void *d_o,
+                          void *dq, void *dk, void *dv,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Token split (Section 4.1, "at the token granularity ... we offload a fraction alpha
+ * to CPU, while the remaining part is discarded").  k = floor(alpha * S) evaluated in
+ * IEEE double; tokens [0,k) are swapped, tokens [k,S) are recomputed by the caller
+ * before the layer's backward.  Returns k, or -1 if S < 0 or alpha is not in [0,1].
+ */
+int64_t memo_split_tokens(int64_t S, double alpha);
+
+typedef struct {
+    int64_t S, row_bytes;
+    int64_t k_swapped;              /* tokens offloaded */
+    int64_t n_recompute;            /* tokens dropped: S - k_swapped */
+    int64_t bytes_swapped;          /* k_swapped * row_bytes */
+    int64_t bytes_dropped;          /* n_recompute * row_bytes */
+    int64_t recompute_byte_offset;  /* where the first dropped row starts in the activation */
+} memo_swap_plan;
+
+/* Fills *out for an activation of S token rows of row_bytes bytes each. */
+memo_status memo_swap_plan_make(int64_t S, int64_t row_bytes, double alpha, memo_swap_plan *out);
+
+/*
+ * Swap-out (Section 4.1: after a layer's computation its saved activations are offloaded
+ * on a separate stream, concurrently with the next computation; an event tells when the
+ * device buffer may be rewritten).
+ *   dev_act      device, [S, row_bytes] bytes, rows contiguous; only rows [0,k) are read
+ *   host_pinned  HOST pinned memory of host_capacity_bytes; receives k*row_bytes bytes
+ *   copy_stream  stream the copy is queued on (the offload stream)
+ *   wait_event   nullable; the copy stream waits for it first (producer finished writing)
+ *   done_event   nullable; recorded on copy_stream after the copy
+ * alpha = 0 queues no copy (events are still honoured).  MEMO_ERR_HOST_CAPACITY if the
+ * host store is too small; then nothing is queued.
+ */
+memo_status memo_swap_out(const void *dev_act, int64_t S, int64_t row_bytes, double alpha,
+                          void *host_pinned, size_t host_capacity_bytes,
+                          void *copy_stream, void *wait_event, void *done_event);
+
+/*
+ * Swap-in (Section 4.1 / 4.3.4: prefetch on a third stream before the layer's backward).
+ * Mirror of memo_swap_out: rows [0,k) of dev_act are written from the host store, rows
+ * [k,S) are not touched.
+ */
+memo_status memo_swap_in(void *dev_act, int64_t S, int64_t row_bytes, double alpha,
+                         const void *host_pinned, size_t host_capacity_bytes,
+                         void *copy_stream, void *wait_event, void *done_event);
+
+/*
+ * Largest alpha in [0,1] with (Section 4.1, the problem "max alpha"):
+ *   (s_in + s_attn + alpha*s_oth) / bandwidth <= t_layer
+ *   (n_layers - 2) * (s_in + s_attn + alpha*s_oth) <= m_cpu
+ * Sizes in bytes, bandwidth in bytes/s, t_layer in s.  Host-side arithmetic only.
+ * Returns MEMO_ERR_HOST_CAPACITY if alpha = 0 already breaks the memory constraint,
+ * MEMO_ERR_UNSUPPORTED if alpha = 0 breaks the time constraint (the copy of the two
+ * whole tensors cannot be hidden), MEMO_ERR_INVALID_ARG on non-positive inputs.
+ */
+memo_status memo_solve_alpha(double s_in, double s_attn, double s_oth, double bandwidth,
+                             double t_layer, int32_t n_layers, double m_cpu, double *alpha_out);
+
+/* Pinned host memory helpers (hipHostMalloc / hipHostFree). */
+memo_status memo_host_alloc(void **host_ptr, size_t bytes);
+memo_status memo_host_free(void *host_ptr);
+
+const char *memo_status_str(memo_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEMO_H */

@@ -1,0 +1,228 @@
+"""Thin ctypes binding of libmemo.so (contract: include/memo.h).
+
+Argument marshalling only: every step of the path runs inside the library's kernels
+and copies.  PyTorch appears only as the owner of device memory, pinned host memory
+and streams.  There is no fallback: if the library is not built, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmemo.so")
+
+MEMO_OK = 0
+MEMO_ERR_INVALID_ARG = 1
+MEMO_ERR_UNSUPPORTED = 2
+MEMO_ERR_HOST_CAPACITY = 3
+MEMO_ERR_WORKSPACE = 4
+MEMO_ERR_DEVICE = 5
+MEMO_F32 = 0
+MEMO_BF16 = 1
+
+EXPORTS = [
+    "memo_attn_fwd", "memo_attn_bwd_workspace_bytes", "memo_attn_bwd", "memo_split_tokens",
+    "memo_swap_plan_make", "memo_swap_out", "memo_swap_in", "memo_solve_alpha",
+    "memo_host_alloc", "memo_host_free", "memo_status_str",
+]
+
+
+class MemoAttnDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("S", ctypes.c_int64), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("stride_b", ctypes.c_int64), ("stride_s", ctypes.c_int64),
+                ("stride_h", ctypes.c_int64), ("causal", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
+
+
+class MemoSwapPlan(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int64), ("row_bytes", ctypes.c_int64),
+                ("k_swapped", ctypes.c_int64), ("n_recompute", ctypes.c_int64),
+                ("bytes_swapped", ctypes.c_int64), ("bytes_dropped", ctypes.c_int64),
+                ("recompute_byte_offset", ctypes.c_int64)]
+
+
+class MemoError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        super().__init__(f"{what}: {status_str(status)} (status {int(status)})")
+
+
+_lib = None
+
+
+def lib():
+    """Loads libmemo.so; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           "`python -c 'import __graft_entry__ as g; g.build()'`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, f64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double, ctypes.c_size_t
+    dp = ctypes.POINTER(MemoAttnDesc)
+    L.memo_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    L.memo_attn_fwd.restype = ctypes.c_int
+    L.memo_attn_bwd_workspace_bytes.argtypes = [dp]
+    L.memo_attn_bwd_workspace_bytes.restype = sz
+    L.memo_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.memo_attn_bwd.restype = ctypes.c_int
+    L.memo_split_tokens.argtypes = [i64, f64]
+    L.memo_split_tokens.restype = i64
+    L.memo_swap_plan_make.argtypes = [i64, i64, f64, ctypes.POINTER(MemoSwapPlan)]
+    L.memo_swap_plan_make.restype = ctypes.c_int
+    L.memo_swap_out.argtypes = [vp, i64, i64, f64, vp, sz, vp, vp, vp]
+    L.memo_swap_out.restype = ctypes.c_int
+    L.memo_swap_in.argtypes = [vp, i64, i64, f64, vp, sz, vp, vp, vp]
+    L.memo_swap_in.restype = ctypes.c_int
+    L.memo_solve_alpha.argtypes = [f64, f64, f64, f64, f64, ctypes.c_int32, f64,
+                                   ctypes.POINTER(ctypes.c_double)]
+    L.memo_solve_alpha.restype = ctypes.c_int
+    L.memo_host_alloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), sz]
+    L.memo_host_alloc.restype = ctypes.c_int
+    L.memo_host_free.argtypes = [vp]
+    L.memo_host_free.restype = ctypes.c_int
+    L.memo_status_str.argtypes = [ctypes.c_int]
+    L.memo_status_str.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def status_str(status):
+    return lib().memo_status_str(int(status)).decode()
+
+
+def _check(status, what):
+    if status != MEMO_OK:
+        raise MemoError(status, what)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _event_ptr(event):
+    if event is None:
+        return None
+    if isinstance(event, int):
+        return event
+    return event.cuda_event
+
+
+def make_desc(q, scale, causal=1, flags=0):
+    """Descriptor for a [B,S,H,d] tensor (any strides with contiguous last dim)."""
+    if q.dim() != 4 or q.stride(3) != 1:
+        raise ValueError("attention tensors must be [B,S,H,d] with contiguous d")
+    dt = {torch.float32: MEMO_F32, torch.bfloat16: MEMO_BF16}.get(q.dtype)
+    if dt is None:
+        raise ValueError(f"unsupported dtype {q.dtype}")
+    B, S, H, d = q.shape
+    return MemoAttnDesc(B=B, H=H, d=d, S=S, dtype=dt, scale=float(scale),
+                        stride_b=q.stride(0), stride_s=q.stride(1), stride_h=q.stride(2),
+                        causal=causal, flags=flags)
+
+
+def _same_layout(ref, *others):
+    for t in others:
+        if t.shape != ref.shape or t.stride() != ref.stride() or t.dtype != ref.dtype:
+            raise ValueError("q, k, v, o, d_o, dq, dk, dv must share shape, strides and dtype")
+        if t.device != ref.device:
+            raise ValueError("tensors must live on one device")
+
+
+def memo_attn_fwd(q, k, v, scale, o=None, lse=None, stream=None):
+    """o, lse = causal softmax attention of q,k,v [B,S,H,d]; lse is [B,H,S] fp32."""
+    B, S, H, d = q.shape
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, S), dtype=torch.float32, device=q.device)
+    _same_layout(q, k, v, o)
+    if lse.dtype != torch.float32 or not lse.is_contiguous() or tuple(lse.shape) != (B, H, S):
+        raise ValueError("lse must be contiguous fp32 [B,H,S]")
+    desc = make_desc(q, scale)
+    st = lib().memo_attn_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                             o.data_ptr(), lse.data_ptr(), _stream_ptr(stream))
+    _check(st, "memo_attn_fwd")
+    return o, lse
+
+
+def memo_attn_bwd_workspace_bytes(q, scale):
+    desc = make_desc(q, scale)
+    return int(lib().memo_attn_bwd_workspace_bytes(ctypes.byref(desc)))
+
+
+def memo_attn_bwd(q, k, v, o, lse, d_o, scale, dq=None, dk=None, dv=None, workspace=None,
+                  stream=None):
+    """dq, dk, dv for dL/dO = d_o.  `workspace`: uint8 device tensor (allocated if None)."""
+    if dq is None:
+        dq = torch.empty_like(q)
+    if dk is None:
+        dk = torch.empty_like(q)
+    if dv is None:
+        dv = torch.empty_like(q)
+    _same_layout(q, k, v, o, d_o, dq, dk, dv)
+    desc = make_desc(q, scale)
+    if workspace is None:
+        need = int(lib().memo_attn_bwd_workspace_bytes(ctypes.byref(desc)))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    st = lib().memo_attn_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                             o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
+                             dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(st, "memo_attn_bwd")
+    return dq, dk, dv
+
+
+def memo_split_tokens(S, alpha):
+    return int(lib().memo_split_tokens(int(S), float(alpha)))
+
+
+def memo_swap_plan_make(S, row_bytes, alpha):
+    plan = MemoSwapPlan()
+    _check(lib().memo_swap_plan_make(int(S), int(row_bytes), float(alpha), ctypes.byref(plan)),
+           "memo_swap_plan_make")
+    return {name: int(getattr(plan, name)) for name, _ in MemoSwapPlan._fields_}
+
+
+def _act_geometry(act):
+    if act.dim() != 2 or not act.is_contiguous():
+        raise ValueError("activation must be a contiguous [S, row] tensor")
+    return act.shape[0], act.shape[1] * act.element_size()
+
+
+def memo_swap_out(dev_act, alpha, host_pinned, copy_stream, wait_event=None, done_event=None):
+    """Queues the D2H copy of the first floor(alpha*S) rows of dev_act [S,row] into the
+    pinned host tensor on copy_stream."""
+    S, row_bytes = _act_geometry(dev_act)
+    if not host_pinned.is_pinned():
+        raise ValueError("host store must be pinned memory")
+    st = lib().memo_swap_out(dev_act.data_ptr(), S, row_bytes, float(alpha),
+                             host_pinned.data_ptr(), host_pinned.numel() * host_pinned.element_size(),
+                             _stream_ptr(copy_stream), _event_ptr(wait_event), _event_ptr(done_event))
+    _check(st, "memo_swap_out")
+
+
+def memo_swap_in(dev_act, alpha, host_pinned, copy_stream, wait_event=None, done_event=None):
+    """Queues the H2D copy of the swapped rows back into rows [0,k) of dev_act."""
+    S, row_bytes = _act_geometry(dev_act)
+    if not host_pinned.is_pinned():
+        raise ValueError("host store must be pinned memory")
+    st = lib().memo_swap_in(dev_act.data_ptr(), S, row_bytes, float(alpha),
+                            host_pinned.data_ptr(), host_pinned.numel() * host_pinned.element_size(),
+                            _stream_ptr(copy_stream), _event_ptr(wait_event), _event_ptr(done_event))
+    _check(st, "memo_swap_in")
+
+
+def memo_solve_alpha(s_in, s_attn, s_oth, bandwidth, t_layer, n_layers, m_cpu):
+    out = ctypes.c_double(0.0)
+    _check(lib().memo_solve_alpha(float(s_in), float(s_attn), float(s_oth), float(bandwidth),
+                                  float(t_layer), int(n_layers), float(m_cpu), ctypes.byref(out)),
+           "memo_solve_alpha")
+    return out.value

@@ -1,0 +1,36 @@
+// Internal interface between the C-ABI front end (memo_api.cpp) and the gfx950 kernels.
+// Not installed; the public contract is include/memo.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace memo {
+
+// One attention problem as the kernels see it.  Element (b, s, h, c) of q/k/v/o/d_o/dq/dk/dv
+// is at b*sb + s*ss + h*sh + c (elements); lse and delta are [B,H,S] fp32.
+struct AttnArgs {
+    const void *q, *k, *v;
+    const void *o_in;     // backward: forward output
+    const void *d_o;      // backward: dL/dO
+    void *o_out;          // forward: output
+    void *dq, *dk, *dv;   // backward outputs
+    float *lse;           // forward: written; backward: read
+    float *delta;         // backward workspace: D_i = sum_c dO_ic O_ic, [B,H,S]
+    int32_t B, H, d;
+    int64_t S;
+    float scale;
+    int64_t sb, ss, sh;
+};
+
+// fp32 path (VALU arithmetic, fp32 throughout), d in {64, 128}
+hipError_t launch_attn_fwd_f32(const AttnArgs &a, hipStream_t st);
+hipError_t launch_attn_bwd_f32(const AttnArgs &a, hipStream_t st);
+
+// bf16 path (bf16 MFMA contractions, fp32 accumulation and softmax), d = 128
+hipError_t launch_attn_fwd_bf16(const AttnArgs &a, hipStream_t st);
+hipError_t launch_attn_bwd_bf16(const AttnArgs &a, hipStream_t st);
+
+// D_i = sum_c dO_ic * O_ic for either dtype (is_bf16 selects the element type)
+hipError_t launch_attn_delta(const AttnArgs &a, bool is_bf16, hipStream_t st);
+
+}  // namespace memo

@@ -1,0 +1,115 @@
+"""GPU parity: the HIP attention path vs the fp64 oracle, element by element, through the
+C-ABI.  Sizes here are ones the dense oracle finishes in seconds; they span several tiles
+(128-row query tiles, 64/128-row key tiles) and ragged tails."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_12117_amd import binding as mb
+from paper_2407_12117_amd import synth
+from gpu_util import LSE_MAX_ABS_BF16, assert_close, gpu_fwd_bwd, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _dense_case(oracle, B, S, H, d, dtype, seed, scale=None):
+    print(f"[case] dense B={B} S={S} H={H} d={d} {dtype} seed={seed}", flush=True)
+    scale = synth.default_scale(d) if scale is None else scale
+    q, k, v, g = synth.attn_inputs(B, S, H, d, dtype, seed)
+    o, lse, dq, dk, dv = gpu_fwd_bwd(*(t.cuda() for t in (q, k, v, g)), scale)
+    qf, kf, vf, gf = (to_f64(t) for t in (q, k, v, g))
+    ro, rlse = oracle.attn_fwd(qf, kf, vf, scale)
+    rdq, rdk, rdv = oracle.attn_bwd(qf, kf, vf, gf, scale)
+    assert_close("O", to_f64(o), ro, dtype)
+    lse_err = np.abs(to_f64(lse) - rlse).max()
+    assert lse_err <= (LSE_MAX_ABS_BF16 if dtype == "bf16" else 1e-4), f"LSE max_abs={lse_err:.3e}"
+    assert_close("dQ", to_f64(dq), rdq, dtype)
+    assert_close("dK", to_f64(dk), rdk, dtype)
+    assert_close("dV", to_f64(dv), rdv, dtype)
+
+
+def test_c1_fp32_dense(oracle):
+    c = synth.CONFIGS["C1"]
+    _dense_case(oracle, c["B"], c["S"], c["H"], c["d"], "f32", synth.config_seed("C1"))
+
+
+@pytest.mark.parametrize("B,S,H,d", [(2, 333, 3, 64), (1, 257, 2, 128), (1, 1, 1, 64), (2, 31, 1, 128)])
+def test_fp32_ragged_and_small(oracle, B, S, H, d):
+    _dense_case(oracle, B, S, H, d, "f32", 7 + S)
+
+
+@pytest.mark.parametrize("S", [1, 2, 31, 63, 64, 65, 127, 128, 129, 200, 777])
+def test_bf16_small_and_ragged(oracle, S):
+    _dense_case(oracle, 2, S, 2, 128, "bf16", 100 + S)
+
+
+@pytest.mark.parametrize("B,S,H", [(1, 2048, 2), (2, 1024, 3), (1, 3000, 1)])
+def test_bf16_multi_tile(oracle, B, S, H):
+    _dense_case(oracle, B, S, H, 128, "bf16", 300 + S)
+
+
+def test_bf16_other_scale(oracle):
+    _dense_case(oracle, 1, 500, 2, 128, "bf16", 41, scale=0.2)
+
+
+def test_bf16_strided_views_of_a_packed_qkv(oracle):
+    # q, k, v as slices of one [B,S,3,H,d] buffer: stride_s = 3*H*d
+    B, S, H, d = 1, 640, 2, 128
+    print(f"[case] packed qkv S={S}", flush=True)
+    scale = synth.default_scale(d)
+    q, k, v, g = synth.attn_inputs(B, S, H, d, "bf16", 55)
+    packed = torch.stack((q, k, v), dim=2).cuda()
+    pg = torch.zeros_like(packed)
+    pg[:, :, 0] = g.cuda()
+    qd, kd, vd, gd = packed[:, :, 0], packed[:, :, 1], packed[:, :, 2], pg[:, :, 0]
+    out = torch.zeros_like(packed)
+    o, lse = mb.memo_attn_fwd(qd, kd, vd, scale, o=out[:, :, 0])
+    grads = torch.zeros_like(packed)
+    dq, dk, dv = mb.memo_attn_bwd(qd, kd, vd, o, lse, gd, scale, dq=grads[:, :, 0], dk=grads[:, :, 1],
+                                  dv=grads[:, :, 2])
+    torch.cuda.synchronize()
+    qf, kf, vf, gf = (to_f64(t) for t in (q, k, v, g))
+    ro, _ = oracle.attn_fwd(qf, kf, vf, scale)
+    rdq, rdk, rdv = oracle.attn_bwd(qf, kf, vf, gf, scale)
+    assert_close("O", to_f64(o), ro, "bf16")
+    assert_close("dQ", to_f64(dq), rdq, "bf16")
+    assert_close("dK", to_f64(dk), rdk, "bf16")
+    assert_close("dV", to_f64(dv), rdv, "bf16")
+    # the untouched slots of the packed output buffers stay zero
+    assert out[:, :, 1:].abs().max().item() == 0.0
+
+
+def test_bf16_constant_values_give_constant_output():
+    # rows of the softmax sum to one: V = 1 -> O = 1 (bf16 rounding of P allows 2^-8)
+    B, S, H, d = 1, 1500, 2, 128
+    q, k, _, _ = synth.attn_inputs(B, S, H, d, "bf16", 77)
+    v = torch.ones_like(q)
+    o, _ = mb.memo_attn_fwd(q.cuda(), k.cuda(), v.cuda(), synth.default_scale(d))
+    torch.cuda.synchronize()
+    assert (o.float() - 1.0).abs().max().item() <= 2 ** -7
+
+
+def test_bf16_causality():
+    # changing keys / values after position p leaves O[:p], LSE[:p] bit-identical
+    B, S, H, d, p = 1, 700, 1, 128, 300
+    q, k, v, _ = (t.cuda() for t in synth.attn_inputs(B, S, H, d, "bf16", 88))
+    scale = synth.default_scale(d)
+    o1, l1 = mb.memo_attn_fwd(q, k, v, scale)
+    k2, v2 = k.clone(), v.clone()
+    k2[:, p:] += 3.0
+    v2[:, p:] -= 2.0
+    o2, l2 = mb.memo_attn_fwd(q, k2, v2, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o1[:, :p], o2[:, :p]) and torch.equal(l1[:, :, :p], l2[:, :, :p])
+    assert not torch.equal(o1[:, p:], o2[:, p:])
+
+
+def test_bf16_is_deterministic():
+    B, S, H, d = 1, 900, 2, 128
+    q, k, v, g = (t.cuda() for t in synth.attn_inputs(B, S, H, d, "bf16", 99))
+    a = gpu_fwd_bwd(q, k, v, g, synth.default_scale(d))
+    b = gpu_fwd_bwd(q, k, v, g, synth.default_scale(d))
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
