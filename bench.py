@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the Memo hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input that is already
+resident in HBM: token split plan, swap-out of the saved activation on the offload stream
+overlapped with the attention forward, swap-in on the prefetch stream overlapped with the
+attention backward (D_i preprocess, dK/dV kernel, dQ kernel).
+
+Prints ONE JSON line: whole-job attention throughput in TFLOP/s (FlashAttention convention for
+causal attention: forward 2*S^2*d*H, backward 5*S^2*d*H), the roofline of the dominant kernel
+measured live with HIP events on the launch stream, the swap/compute overlap, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "attn fwd+bwd TFLOP/s (% bf16 MFMA peak) at S=256K/1M; swap-overlap fraction"
+BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
+
+
+def cpu_baseline(cfg, q, k, v, g, scale, budget_s=15.0):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
+    exact forward + dQ rows of head 0 at uniformly spaced query positions."""
+    import numpy as np
+    from oracle import memo_oracle
+    S, d = cfg["S"], cfg["d"]
+    f64 = lambda t: t[0, :, 0, :].to("cpu").double().numpy()
+    qh, kh, vh, gh = f64(q), f64(k), f64(v), f64(g)
+    threads = memo_oracle.num_threads()
+
+    def rows_for(n):
+        return np.unique(np.linspace(0, S - 1, n + 2)[1:-1].astype(np.int64))
+
+    def run(rows):
+        t0 = time.perf_counter()
+        memo_oracle.head_rows(qh, kh, vh, gh, rows, scale)
+        dt = time.perf_counter() - t0
+        # per row i: scores, P.V, dP, dQ over i+1 keys -> 4 contractions of 2*d flops each
+        return dt, float(((rows + 1) * 8.0 * d).sum())
+
+    rows = rows_for(threads)
+    dt, fl = run(rows)                                   # calibration pass (counts as warm-up)
+    n = int(max(threads, min(4096, len(rows) * budget_s / max(dt, 1e-3))))
+    rows = rows_for(n)
+    dt, fl = run(rows)
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"fp64 oracle forward+dQ of {len(rows)} uniformly spaced query rows of head 0 "
+                      f"at S={S}, d={d} ({fl / 1e9:.1f} GFLOP in {dt:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C5", help="workload C2..C5 (default: the 1M-token one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one GPU's share of a tensor-parallel layer); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2407_12117_amd import binding as mb
+    from paper_2407_12117_amd import synth
+
+    mb.lib()                                             # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    assert cfg["dtype"] == "bf16", "bench workloads are the bf16 ones (C2..C5)"
+    B, S, H, d = cfg["B"], cfg["S"], cfg["H"], cfg["d"]
+    row_bytes, alpha = cfg["act_cols"] * cfg["act_elem"], cfg["alpha"]
+    scale = synth.default_scale(d)
+    seed = synth.config_seed(args.config)
+
+    q, k, v, g = synth.attn_inputs(B, S, H, d, "bf16", seed, device="cuda")
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    ws = torch.empty(mb.memo_attn_bwd_workspace_bytes(q, scale), dtype=torch.uint8, device="cuda")
+    act = synth.activation(S, row_bytes, seed, device="cuda")
+    act_back = torch.empty_like(act)
+    plan = mb.memo_swap_plan_make(S, row_bytes, alpha)
+    host = torch.empty(max(plan["bytes_swapped"], 1), dtype=torch.uint8, pin_memory=True)
+
+    compute = torch.cuda.current_stream()
+    offload, prefetch = torch.cuda.Stream(), torch.cuda.Stream()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(rec=None):
+        """rec: dict to receive this step's timing events (None during warm-up)."""
+        mb.memo_swap_plan_make(S, row_bytes, alpha)
+        produced, offloaded, fetched = ev(), ev(), ev()
+        f0, f1 = ev(), ev()
+        stages = [ev() for _ in range(4)]
+        produced.record(compute)
+        mb.memo_swap_out(act, alpha, host, offload, wait_event=produced, done_event=offloaded)
+        f0.record(compute)
+        mb.memo_attn_fwd(q, k, v, scale, o=o, lse=lse)
+        f1.record(compute)
+        # backward of the layer: prefetch the swapped tokens while attention backward runs
+        mb.memo_swap_in(act_back, alpha, host, prefetch, wait_event=offloaded, done_event=fetched)
+        mb.memo_attn_bwd(q, k, v, o, lse, g, scale, dq=dq, dk=dk, dv=dv, workspace=ws, stage_events=stages)
+        compute.wait_event(fetched)                      # the consumer of the activation waits here
+        if rec is not None:
+            rec.setdefault("fwd", []).append((f0, f1))
+            rec.setdefault("stages", []).append(stages)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rec = {}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(rec)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    pairs = float(S) * float(S)                          # 2 * (S^2/2 causal pairs)
+    fwd_flop = 2.0 * pairs * d * H * B
+    bwd_flop = 5.0 * pairs * d * H * B
+    value = (fwd_flop + bwd_flop) / (ms_per_step * 1e-3) / 1e12
+
+    mean = lambda xs: sum(xs) / len(xs)
+    fwd_ms = mean([a.elapsed_time(b) for a, b in rec["fwd"]])
+    delta_ms = mean([s[0].elapsed_time(s[1]) for s in rec["stages"]])
+    dkdv_ms = mean([s[1].elapsed_time(s[2]) for s in rec["stages"]])
+    dq_ms = mean([s[2].elapsed_time(s[3]) for s in rec["stages"]])
+    # contractions each kernel executes (2*d flops per visible (i,j) pair and contraction):
+    # forward 2 (QK^T, PV); dK/dV kernel 4 (QK^T, dO V^T, P^T dO, dS^T Q); dQ kernel 3
+    kernels = {
+        "attn_fwd_bf16_kernel": (fwd_ms, 2.0 * pairs * d * H * B),
+        "attn_bwd_dkdv_bf16_kernel": (dkdv_ms, 4.0 * pairs * d * H * B),
+        "attn_bwd_dq_bf16_kernel": (dq_ms, 3.0 * pairs * d * H * B),
+    }
+    dom = max(kernels, key=lambda n: kernels[n][0])
+    dom_ms, dom_flop = kernels[dom]
+    achieved = dom_flop / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                "avg_launch_ms": dom_ms,
+                "all_kernels": {n: {"avg_ms": ms, "TFLOP/s": fl / (ms * 1e-3) / 1e12,
+                                    "frac": fl / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+                                for n, (ms, fl) in kernels.items()},
+                "delta_kernel_ms": delta_ms}
+
+    # ---- swap/compute overlap, measured outside the timed steps -------------------------
+    def timed(fn, stream_sync=True):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3
+
+    def copy_out():
+        e0 = ev(); e0.record(compute)
+        mb.memo_swap_out(act, alpha, host, offload, wait_event=e0)
+
+    def copy_in():
+        e0 = ev(); e0.record(compute)
+        mb.memo_swap_in(act_back, alpha, host, prefetch, wait_event=e0)
+
+    def fwd_only():
+        mb.memo_attn_fwd(q, k, v, scale, o=o, lse=lse)
+
+    def bwd_only():
+        mb.memo_attn_bwd(q, k, v, o, lse, g, scale, dq=dq, dk=dk, dv=dv, workspace=ws)
+
+    t_out, t_in = timed(copy_out), timed(copy_in)
+    t_f, t_b = timed(fwd_only), timed(bwd_only)
+    t_f_out = timed(lambda: (copy_out(), fwd_only()))
+    t_b_in = timed(lambda: (copy_in(), bwd_only()))
+    nbytes = plan["bytes_swapped"]
+    hidden = lambda ta, tc, tac: max(0.0, min(1.0, (ta + tc - tac) / tc)) if tc > 0 else 1.0
+    swap = {
+        "bytes_swapped": nbytes, "alpha": alpha, "k_swapped": plan["k_swapped"],
+        "d2h_GBps": nbytes / (t_out * 1e-3) / 1e9 if nbytes else None,
+        "h2d_GBps": nbytes / (t_in * 1e-3) / 1e9 if nbytes else None,
+        "swap_out_ms": t_out, "swap_in_ms": t_in, "fwd_alone_ms": t_f, "bwd_alone_ms": t_b,
+        "fwd_with_swap_out_ms": t_f_out, "bwd_with_swap_in_ms": t_b_in,
+        "hidden_fraction_swap_out": hidden(t_f, t_out, t_f_out),
+        "hidden_fraction_swap_in": hidden(t_b, t_in, t_b_in),
+        "attn_slowdown_fwd": t_f_out / t_f if t_f_out > t_f else 1.0,
+        "attn_slowdown_bwd": t_b_in / t_b if t_b_in > t_b else 1.0,
+    }
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: causal attention fwd+bwd B={B} H={H} S={S} d={d} bf16 "
+                               f"N(0,1) q/k/v/dO + token-wise swap of a {S}x{cfg['act_cols']} bf16 "
+                               f"activation, alpha={alpha}",
+                   "flop_convention": "causal: fwd 2*S^2*d*H, bwd 5*S^2*d*H",
+                   "frac_of_bf16_mfma_peak": value / BF16_MFMA_PEAK_TFLOPS,
+                   "mfu_convention_TFLOPs": 6.0 * pairs * d * H * B / (ms_per_step * 1e-3) / 1e12},
+        "roofline": roofline,
+        "swap": swap,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, g, scale)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -85,6 +85,21 @@ memo_status memo_attn_bwd(const memo_attn_desc *desc, const void *q, const void 
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Same as memo_attn_bwd, and additionally records caller-owned events on `stream` between the
+ * stages of the backward, so that a profiler or benchmark can time each kernel where it runs:
+ *   stage_events[0] before the first kernel,
+ *   stage_events[1] after the D_i = sum_c dO_ic O_ic preprocess,
+ *   stage_events[2] after the dK/dV kernel,
+ *   stage_events[3] after the dQ kernel.
+ * stage_events is a host array of 4 hipEvent_t (created with timing enabled), or NULL.
+ */
+memo_status memo_attn_bwd_staged(const memo_attn_desc *desc, const void *q, const void *k,
+                                 const void *v, const void *o, const float *lse, const void *d_o,
+                                 void *dq, void *dk, void *dv,
+                                 void *workspace, size_t workspace_bytes, void *stream,
+                                 void *const *stage_events);
+
+/*
  * Token split (Section 4.1, "at the token granularity ... we offload a fraction alpha
  * to CPU, while the remaining part is discarded").  k = floor(alpha * S) evaluated in
  * IEEE double; tokens [0,k) are swapped, tokens [k,S) are recomputed by the caller

@@ -22,7 +22,8 @@ MEMO_F32 = 0
 MEMO_BF16 = 1
 
 EXPORTS = [
-    "memo_attn_fwd", "memo_attn_bwd_workspace_bytes", "memo_attn_bwd", "memo_split_tokens",
+    "memo_attn_fwd", "memo_attn_bwd_workspace_bytes", "memo_attn_bwd", "memo_attn_bwd_staged",
+    "memo_split_tokens",
     "memo_swap_plan_make", "memo_swap_out", "memo_swap_in", "memo_solve_alpha",
     "memo_host_alloc", "memo_host_free", "memo_status_str",
 ]
@@ -69,6 +70,9 @@ def lib():
     L.memo_attn_bwd_workspace_bytes.restype = sz
     L.memo_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.memo_attn_bwd.restype = ctypes.c_int
+    L.memo_attn_bwd_staged.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
+                                       ctypes.POINTER(ctypes.c_void_p)]
+    L.memo_attn_bwd_staged.restype = ctypes.c_int
     L.memo_split_tokens.argtypes = [i64, f64]
     L.memo_split_tokens.restype = i64
     L.memo_swap_plan_make.argtypes = [i64, i64, f64, ctypes.POINTER(MemoSwapPlan)]
@@ -107,12 +111,24 @@ def _stream_ptr(stream):
     return stream.cuda_stream
 
 
-def _event_ptr(event):
+def _event_ptr(event, create_on=None):
+    """hipEvent_t of a torch event.  torch creates the handle lazily at the first record():
+    an event the library is to record (create_on = that stream) is recorded once here to
+    bring the handle into being (the library's later record supersedes it); an event the
+    library is to WAIT for must already have been recorded by its producer."""
     if event is None:
         return None
     if isinstance(event, int):
         return event
+    if not event.cuda_event:
+        if create_on is None:
+            raise ValueError("wait_event has never been recorded: there is nothing to wait for")
+        event.record(create_on if not isinstance(create_on, int) else None)
     return event.cuda_event
+
+
+def _stream_obj(stream):
+    return torch.cuda.current_stream() if stream is None else stream
 
 
 def make_desc(q, scale, causal=1, flags=0):
@@ -159,8 +175,9 @@ def memo_attn_bwd_workspace_bytes(q, scale):
 
 
 def memo_attn_bwd(q, k, v, o, lse, d_o, scale, dq=None, dk=None, dv=None, workspace=None,
-                  stream=None):
-    """dq, dk, dv for dL/dO = d_o.  `workspace`: uint8 device tensor (allocated if None)."""
+                  stream=None, stage_events=None):
+    """dq, dk, dv for dL/dO = d_o.  `workspace`: uint8 device tensor (allocated if None).
+    stage_events: optional 4 torch.cuda.Event(enable_timing=True), passed to memo_attn_bwd_staged."""
     if dq is None:
         dq = torch.empty_like(q)
     if dk is None:
@@ -172,10 +189,17 @@ def memo_attn_bwd(q, k, v, o, lse, d_o, scale, dq=None, dk=None, dv=None, worksp
     if workspace is None:
         need = int(lib().memo_attn_bwd_workspace_bytes(ctypes.byref(desc)))
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    st = lib().memo_attn_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
-                             o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
-                             dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
-                             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    args = (ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+            o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
+            dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    if stage_events is None:
+        st = lib().memo_attn_bwd(*args)
+    else:
+        if len(stage_events) != 4:
+            raise ValueError("stage_events must hold 4 events")
+        handles = (ctypes.c_void_p * 4)(*[_event_ptr(e, _stream_obj(stream)) for e in stage_events])
+        st = lib().memo_attn_bwd_staged(*args, handles)
     _check(st, "memo_attn_bwd")
     return dq, dk, dv
 
@@ -205,7 +229,8 @@ def memo_swap_out(dev_act, alpha, host_pinned, copy_stream, wait_event=None, don
         raise ValueError("host store must be pinned memory")
     st = lib().memo_swap_out(dev_act.data_ptr(), S, row_bytes, float(alpha),
                              host_pinned.data_ptr(), host_pinned.numel() * host_pinned.element_size(),
-                             _stream_ptr(copy_stream), _event_ptr(wait_event), _event_ptr(done_event))
+                             _stream_ptr(copy_stream), _event_ptr(wait_event),
+                             _event_ptr(done_event, _stream_obj(copy_stream)))
     _check(st, "memo_swap_out")
 
 
@@ -216,7 +241,8 @@ def memo_swap_in(dev_act, alpha, host_pinned, copy_stream, wait_event=None, done
         raise ValueError("host store must be pinned memory")
     st = lib().memo_swap_in(dev_act.data_ptr(), S, row_bytes, float(alpha),
                             host_pinned.data_ptr(), host_pinned.numel() * host_pinned.element_size(),
-                            _stream_ptr(copy_stream), _event_ptr(wait_event), _event_ptr(done_event))
+                            _stream_ptr(copy_stream), _event_ptr(wait_event),
+                            _event_ptr(done_event, _stream_obj(copy_stream)))
     _check(st, "memo_swap_in")
 
 

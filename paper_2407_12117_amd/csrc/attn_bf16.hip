@@ -523,13 +523,17 @@ hipError_t launch_attn_fwd_bf16(const AttnArgs &a, hipStream_t st)
 
 hipError_t launch_attn_bwd_bf16(const AttnArgs &a, hipStream_t st)
 {
-    hipError_t e = launch_attn_delta(a, true, st);
-    if (e != hipSuccess) return e;
     const int64_t nqt = (a.S + kFwdBq - 1) / kFwdBq;
     const int64_t nkt = (a.S + kBwdBk - 1) / kBwdBk;
     if (nqt * a.H * a.B > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipError_t e = record_stage(a, 0, st);
+    if (e != hipSuccess) return e;
+    if ((e = launch_attn_delta(a, true, st)) != hipSuccess) return e;
+    if ((e = record_stage(a, 1, st)) != hipSuccess) return e;
     attn_bwd_dkdv_bf16_kernel<<<dim3((unsigned)(nkt * a.H * a.B)), 256, 0, st>>>(a);
+    if ((e = record_stage(a, 2, st)) != hipSuccess) return e;
     attn_bwd_dq_bf16_kernel<<<dim3((unsigned)(nqt * a.H * a.B)), 256, 0, st>>>(a);
+    if ((e = record_stage(a, 3, st)) != hipSuccess) return e;
     return hipGetLastError();
 }
 

@@ -298,15 +298,21 @@ hipError_t launch_attn_delta(const AttnArgs &a, bool is_bf16, hipStream_t st)
 
 hipError_t launch_attn_bwd_f32(const AttnArgs &a, hipStream_t st)
 {
-    hipError_t e = launch_attn_delta(a, false, st);
+    hipError_t e = record_stage(a, 0, st);
     if (e != hipSuccess) return e;
-    if (a.d == 64) {
-        attn_bwd_dq_f32_kernel<64><<<row_grid(a, kRows), 256, 0, st>>>(a);
+    e = launch_attn_delta(a, false, st);
+    if (e != hipSuccess) return e;
+    if ((e = record_stage(a, 1, st)) != hipSuccess) return e;
+    if (a.d == 64)
         attn_bwd_dkdv_f32_kernel<64><<<row_grid(a, kRows), 256, 0, st>>>(a);
-    } else {
-        attn_bwd_dq_f32_kernel<128><<<row_grid(a, kRows), 256, 0, st>>>(a);
+    else
         attn_bwd_dkdv_f32_kernel<128><<<row_grid(a, kRows), 256, 0, st>>>(a);
-    }
+    if ((e = record_stage(a, 2, st)) != hipSuccess) return e;
+    if (a.d == 64)
+        attn_bwd_dq_f32_kernel<64><<<row_grid(a, kRows), 256, 0, st>>>(a);
+    else
+        attn_bwd_dq_f32_kernel<128><<<row_grid(a, kRows), 256, 0, st>>>(a);
+    if ((e = record_stage(a, 3, st)) != hipSuccess) return e;
     return hipGetLastError();
 }
 

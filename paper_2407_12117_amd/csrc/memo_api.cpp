@@ -100,6 +100,16 @@ memo_status memo_attn_bwd(const memo_attn_desc *desc, const void *q, const void 
                           void *dq, void *dk, void *dv,
                           void *workspace, size_t workspace_bytes, void *stream)
 {
+    return memo_attn_bwd_staged(desc, q, k, v, o, lse, d_o, dq, dk, dv, workspace, workspace_bytes,
+                                stream, nullptr);
+}
+
+memo_status memo_attn_bwd_staged(const memo_attn_desc *desc, const void *q, const void *k,
+                                 const void *v, const void *o, const float *lse, const void *d_o,
+                                 void *dq, void *dk, void *dv,
+                                 void *workspace, size_t workspace_bytes, void *stream,
+                                 void *const *stage_events)
+{
     memo::AttnArgs a;
     memo_status st = check_desc(desc, &a);
     if (st != MEMO_OK) return st;
@@ -120,6 +130,14 @@ memo_status memo_attn_bwd(const memo_attn_desc *desc, const void *q, const void 
     a.dv = dv;
     a.lse = const_cast<float *>(lse);
     a.delta = static_cast<float *>(workspace);
+    hipEvent_t events[4];
+    if (stage_events) {
+        for (int n = 0; n < 4; ++n) {
+            if (!stage_events[n]) return MEMO_ERR_INVALID_ARG;
+            events[n] = static_cast<hipEvent_t>(stage_events[n]);
+        }
+        a.stage_events = events;
+    }
     hipStream_t hs = static_cast<hipStream_t>(stream);
     hipError_t e = desc->dtype == MEMO_BF16 ? memo::launch_attn_bwd_bf16(a, hs)
                                             : memo::launch_attn_bwd_f32(a, hs);

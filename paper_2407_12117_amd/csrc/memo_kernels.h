@@ -20,7 +20,13 @@ struct AttnArgs {
     int64_t S;
     float scale;
     int64_t sb, ss, sh;
+    hipEvent_t *stage_events;   // backward only, nullable: 4 events recorded between the stages
 };
+
+inline hipError_t record_stage(const AttnArgs &a, int idx, hipStream_t st)
+{
+    return a.stage_events ? hipEventRecord(a.stage_events[idx], st) : hipSuccess;
+}
 
 // fp32 path (VALU arithmetic, fp32 throughout), d in {64, 128}
 hipError_t launch_attn_fwd_f32(const AttnArgs &a, hipStream_t st);

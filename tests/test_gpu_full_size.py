@@ -1,0 +1,140 @@
+"""GPU parity at the full workload sizes, in the launch configuration the benchmark times.
+
+The dense oracle would take hours to days here, so each workload is pinned by
+  (a) exact oracle rows: O, LSE, dQ of sampled query rows (cost O(i*d) each),
+  (b) exact oracle columns: dK, dV of the last key columns (needs only the last rows),
+  (c) invariants of the full tensors: sum_j dV_j = sum_i dO_i, sum q.dQ = sum k.dK per head,
+  (d) closed forms on every tile: V = 1 -> O = 1; Q = 0 -> O = prefix mean of V,
+      LSE = ln(i+1), dV_j = sum_{i>=j} dO_i/(i+1), dK = 0,
+  (e) the swap of the workload's activation, overlapped with the forward, byte for byte
+      against the oracle's memcpy bookkeeping.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_12117_amd import binding as mb
+from paper_2407_12117_amd import synth
+from gpu_util import BF16_MAX_ABS, BF16_REL_L2, LSE_MAX_ABS_BF16, assert_close, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(S, rng):
+    fixed = [0, 1, 31, 32, 63, 64, 127, 128, 129, S // 2 - 1, S // 2, S - 129, S - 128, S - 2, S - 1]
+    rand = rng.integers(0, S, size=9).tolist()
+    return np.array(sorted(set(r for r in fixed + rand if 0 <= r < S)), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_workload_sampled_parity(oracle, name):
+    cfg = synth.CONFIGS[name]
+    B, S, H, d = cfg["B"], cfg["S"], cfg["H"], cfg["d"]
+    seed = synth.config_seed(name)
+    scale = synth.default_scale(d)
+    print(f"[case] {name}: B={B} H={H} S={S} d={d} seed={seed}", flush=True)
+    q, k, v, g = synth.attn_inputs(B, S, H, d, "bf16", seed, device="cuda")
+    o, lse = mb.memo_attn_fwd(q, k, v, scale)
+    dq, dk, dv = mb.memo_attn_bwd(q, k, v, o, lse, g, scale)
+    torch.cuda.synchronize()
+    print("[step] kernels done", flush=True)
+    for t in (o, lse, dq, dk, dv):
+        assert torch.isfinite(t).all()
+
+    rng = np.random.default_rng(seed)
+    rows = _sample_rows(S, rng)
+    tail = 160 if S <= 262144 else 40
+    for h in sorted({0, H - 1}):
+        qh, kh, vh, gh = (to_f64(t[0, :, h, :]) for t in (q, k, v, g))
+        ro, rlse, _, rdq = oracle.head_rows(qh, kh, vh, gh, rows, scale)
+        assert_close(f"{name} h{h} O rows", to_f64(o[0, rows, h, :]), ro, "bf16")
+        assert_close(f"{name} h{h} dQ rows", to_f64(dq[0, rows, h, :]), rdq, "bf16")
+        lse_err = np.abs(to_f64(lse[0, h, rows]) - rlse).max()
+        assert lse_err <= LSE_MAX_ABS_BF16, f"{name} h{h} LSE max_abs={lse_err:.3e}"
+        print(f"[step] head {h} rows ok", flush=True)
+        rdk, rdv = oracle.head_dkdv_tail(qh, kh, vh, gh, S - tail, scale)
+        assert_close(f"{name} h{h} dK tail", to_f64(dk[0, S - tail:, h, :]), rdk, "bf16")
+        assert_close(f"{name} h{h} dV tail", to_f64(dv[0, S - tail:, h, :]), rdv, "bf16")
+        print(f"[step] head {h} tail columns ok", flush=True)
+        del qh, kh, vh, gh
+
+    # (c) invariants over the whole tensors, accumulated in fp64 on the device
+    sum_dv = dv.double().sum(dim=1)
+    sum_do = g.double().sum(dim=1)
+    rel = ((sum_dv - sum_do).norm() / sum_do.norm()).item()
+    assert rel <= BF16_REL_L2, f"{name}: sum dV vs sum dO rel={rel:.3e}"
+    r_i = (q.double() * dq.double()).sum(dim=3)          # [B,S,H]
+    c_j = (k.double() * dk.double()).sum(dim=3)
+    a, b = r_i.sum(dim=1), c_j.sum(dim=1)                # [B,H]
+    noise = 2.0 ** -8 * torch.sqrt((r_i ** 2).sum(dim=1) + (c_j ** 2).sum(dim=1))
+    assert ((a - b).abs() <= 6.0 * noise + 1e-3).all(), f"{name}: q.dQ={a.tolist()} k.dK={b.tolist()}"
+
+
+@pytest.mark.parametrize("name", ["C2", "C4"])
+def test_workload_closed_forms(name):
+    cfg = synth.CONFIGS[name]
+    B, S, H, d = cfg["B"], cfg["S"], cfg["H"], cfg["d"]
+    scale = synth.default_scale(d)
+    print(f"[case] closed forms {name}", flush=True)
+    _, k, v, g = synth.attn_inputs(B, S, H, d, "bf16", synth.config_seed(name) + 50, device="cuda")
+    q = torch.zeros_like(k)
+    o, lse = mb.memo_attn_fwd(q, k, v, scale)
+    dq, dk, dv = mb.memo_attn_bwd(q, k, v, o, lse, g, scale)
+    torch.cuda.synchronize()
+    n = torch.arange(1, S + 1, dtype=torch.float64, device="cuda")
+    want_o = v.double().cumsum(dim=1) / n[None, :, None, None]
+    err = (o.double() - want_o).abs().max().item()
+    assert err <= BF16_MAX_ABS, f"O vs prefix mean: {err:.3e}"
+    lse_err = (lse.double() - torch.log(n)[None, None, :]).abs().max().item()
+    assert lse_err <= LSE_MAX_ABS_BF16, f"LSE vs ln(i+1): {lse_err:.3e}"
+    assert dk.abs().max().item() == 0.0
+    w = g.double() / n[None, :, None, None]
+    want_dv = torch.flip(torch.cumsum(torch.flip(w, dims=[1]), dim=1), dims=[1])
+    diff = dv.double() - want_dv
+    assert diff.abs().max().item() <= BF16_MAX_ABS, f"dV max_abs={diff.abs().max().item():.3e}"
+    assert (diff.norm() / want_dv.norm()).item() <= BF16_REL_L2
+    # rows of the softmax sum to one on every tile
+    ones = torch.ones_like(k)
+    q2, _, _, _ = synth.attn_inputs(B, S, H, d, "bf16", synth.config_seed(name) + 60, device="cuda")
+    o1, _ = mb.memo_attn_fwd(q2, k, ones, scale)
+    torch.cuda.synchronize()
+    assert (o1.float() - 1.0).abs().max().item() <= 2 ** -7
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_workload_swap_overlapped_with_forward(oracle, name):
+    cfg = synth.CONFIGS[name]
+    B, S, H, d = cfg["B"], cfg["S"], cfg["H"], cfg["d"]
+    row_bytes, alpha = cfg["act_cols"] * cfg["act_elem"], cfg["alpha"]
+    print(f"[case] swap {name}: S={S} row_bytes={row_bytes} alpha={alpha}", flush=True)
+    scale = synth.default_scale(d)
+    seed = synth.config_seed(name)
+    plan = mb.memo_swap_plan_make(S, row_bytes, alpha)
+    assert plan == dict(S=S, row_bytes=row_bytes, **oracle.swap_plan(S, row_bytes, alpha))
+    act = synth.activation(S, row_bytes, seed, device="cuda")
+    host = torch.empty(max(plan["bytes_swapped"], 1), dtype=torch.uint8, pin_memory=True)
+    q, k, v, _ = synth.attn_inputs(B, min(S, 131072), H, d, "bf16", seed, device="cuda")
+    side = torch.cuda.Stream()
+    ready, done = torch.cuda.Event(), torch.cuda.Event()
+    torch.cuda.synchronize()
+    ready.record()
+    mb.memo_swap_out(act, alpha, host, side, wait_event=ready, done_event=done)
+    mb.memo_attn_fwd(q, k, v, scale)                     # compute stream keeps working meanwhile
+    done.synchronize()
+    print("[step] swap-out done", flush=True)
+    act_np = act.cpu().numpy().reshape(-1)
+    ref_host = np.zeros(max(plan["bytes_swapped"], 1), dtype=np.uint8)
+    n = oracle.swap_out(act_np, row_bytes, alpha, ref_host)
+    assert n == plan["bytes_swapped"]
+    assert np.array_equal(host.numpy()[:n], ref_host[:n])
+    del ref_host
+    # swap-in into a poisoned buffer: swapped rows return, dropped rows stay untouched
+    back = torch.full_like(act, 0x5A)
+    poisoned = torch.cuda.Event()
+    poisoned.record()                                    # the copy stream must not overtake the fill
+    mb.memo_swap_in(back, alpha, host, side, wait_event=poisoned, done_event=done)
+    done.synchronize()
+    kk = plan["k_swapped"]
+    assert torch.equal(back[:kk], act[:kk])
+    assert (back[kk:] == 0x5A).all()
+    torch.cuda.synchronize()

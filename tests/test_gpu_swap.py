@@ -40,8 +40,9 @@ def test_round_trip_matches_oracle(oracle, alpha, S, row_bytes):
 
     # forward is over: the device buffer is reused (poisoned), then the swapped rows return
     restored = torch.full_like(act, 0x5A)
-    done2 = torch.cuda.Event()
-    mb.memo_swap_in(restored, alpha, host, side, done_event=done2)
+    poisoned, done2 = torch.cuda.Event(), torch.cuda.Event()
+    poisoned.record()                      # the copy stream must not overtake the fill
+    mb.memo_swap_in(restored, alpha, host, side, wait_event=poisoned, done_event=done2)
     done2.synchronize()
     ref_restored = np.full(S * row_bytes, 0x5A, dtype=np.uint8)
     oracle.swap_in(ref_restored, row_bytes, alpha, ref_host)
@@ -63,7 +64,9 @@ def test_c1_activation_fp32(oracle):
     assert k == 512
     assert torch.equal(host[:k], act[:k].cpu()) and host[k:].abs().max().item() == 0.0
     back = torch.full_like(act, float("nan"))
-    mb.memo_swap_in(back, c["alpha"], host, side, done_event=ev)
+    filled = torch.cuda.Event()
+    filled.record()
+    mb.memo_swap_in(back, c["alpha"], host, side, wait_event=filled, done_event=ev)
     ev.synchronize()
     assert torch.equal(back[:k], act[:k]) and torch.isnan(back[k:]).all()
 
