@@ -62,6 +62,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C5", help="workload C2..C5 (default: the 1M-token one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="skip the separate swap/compute overlap measurement (profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy kernel (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one GPU's share of a tensor-parallel layer); "
@@ -176,6 +180,35 @@ def main():
     def bwd_only():
         mb.memo_attn_bwd(q, k, v, o, lse, g, scale, dq=dq, dk=dk, dv=dv, workspace=ws)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                   # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+    if args.no_overlap:
+        swap = None
+    else:
+        swap = measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, plan, alpha)
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: causal attention fwd+bwd B={B} H={H} S={S} d={d} bf16 "
+                               f"N(0,1) q/k/v/dO + token-wise swap of a {S}x{cfg['act_cols']} bf16 "
+                               f"activation, alpha={alpha}",
+                   "flop_convention": "causal: fwd 2*S^2*d*H, bwd 5*S^2*d*H",
+                   "frac_of_bf16_mfma_peak": value / BF16_MFMA_PEAK_TFLOPS,
+                   "mfu_convention_TFLOPs": 6.0 * pairs * d * H * B / (ms_per_step * 1e-3) / 1e12},
+        "roofline": roofline,
+        "swap": swap,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, g, scale)
+    print(json.dumps(out), flush=True)
+
+
+def measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, plan, alpha):
     t_out, t_in = timed(copy_out), timed(copy_in)
     t_f, t_b = timed(fwd_only), timed(bwd_only)
     t_f_out = timed(lambda: (copy_out(), fwd_only()))
@@ -194,22 +227,7 @@ def main():
         "attn_slowdown_bwd": t_b_in / t_b if t_b_in > t_b else 1.0,
     }
 
-    out = {
-        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: causal attention fwd+bwd B={B} H={H} S={S} d={d} bf16 "
-                               f"N(0,1) q/k/v/dO + token-wise swap of a {S}x{cfg['act_cols']} bf16 "
-                               f"activation, alpha={alpha}",
-                   "flop_convention": "causal: fwd 2*S^2*d*H, bwd 5*S^2*d*H",
-                   "frac_of_bf16_mfma_peak": value / BF16_MFMA_PEAK_TFLOPS,
-                   "mfu_convention_TFLOPs": 6.0 * pairs * d * H * B / (ms_per_step * 1e-3) / 1e12},
-        "roofline": roofline,
-        "swap": swap,
-    }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, g, scale)
-    print(json.dumps(out), flush=True)
+    return swap
 
 
 if __name__ == "__main__":

@@ -43,6 +43,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 #define LDS_AS __attribute__((address_space(3)))
+#define GLB_AS __attribute__((address_space(1)))
 
 constexpr int kTileBytes = 64 * 256;   // one 64 x 128 bf16 tile
 constexpr float kLog2e = 1.4426950408889634f;
@@ -174,15 +175,98 @@ __device__ __forceinline__ TileId decode_block(const AttnArgs &a, int64_t ntiles
     return t;
 }
 
+// ---- asynchronous tile fill: global -> LDS without passing through registers -------------
+// One global_load_lds_dwordx4 moves 64 x 16 bytes: lane l lands at LDS base + 16*l, i.e. four
+// tile rows of sixteen chunks.  Wave w issues instruction n for tile rows 16w + 4n + l/16; the
+// lane at chunk position p = l%16 fetches logical chunk p ^ swz(row), so the swizzle is applied
+// on the global side.  Offsets are 32-bit from a wave-uniform tile base (scalar base + vector
+// offset addressing): no per-tile vector address arithmetic.
+template <int NW>      // NW waves share the 16 fill instructions of a 64-row tile
+struct TileFill {
+    static constexpr int kInstr = 16 / NW;
+    uint32_t goff[16 / NW];   // byte offset of this lane's 16 bytes from the tile's first row, per n
+};
+
+template <int NW>
+__device__ __forceinline__ TileFill<NW> make_tile_fill(int wave, int lane, int64_t ss)
+{
+    TileFill<NW> f;
+#pragma unroll
+    for (int n = 0; n < TileFill<NW>::kInstr; ++n) {
+        const int row = 4 * (TileFill<NW>::kInstr * wave + n) + (lane >> 4);
+        const int chunk = (lane & 15) ^ swz(row);
+        f.goff[n] = (uint32_t)((row * ss + chunk * 8) * 2);
+    }
+    return f;
+}
+
+// Queues the fill of one 64-row tile starting at row r0 of the head view `src`.  Rows past S
+// re-read row S-1 (finite values; every consumer masks them).  r0, S, src are wave-uniform.
+template <int NW>
+__device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, const __bf16 *src, int64_t ss,
+                                                int64_t r0, int64_t S, const TileFill<NW> &f, int wave,
+                                                int lane)
+{
+    constexpr int NI = TileFill<NW>::kInstr;
+    if (r0 + 64 <= S) {
+        const char *tb = reinterpret_cast<const char *>(src + r0 * ss);
+#pragma unroll
+        for (int n = 0; n < NI; ++n)
+            __builtin_amdgcn_global_load_lds((const GLB_AS void *)(tb + f.goff[n]),
+                                             (LDS_AS void *)(tile + (NI * wave + n) * 1024), 16, 0, 0);
+    } else {
+#pragma unroll
+        for (int n = 0; n < NI; ++n) {
+            const int row = 4 * (NI * wave + n) + (lane >> 4);
+            const int chunk = (lane & 15) ^ swz(row);
+            int64_t rg = r0 + row;
+            rg = rg < S ? rg : S - 1;
+            __builtin_amdgcn_global_load_lds((const GLB_AS void *)(src + rg * ss + chunk * 8),
+                                             (LDS_AS void *)(tile + (NI * wave + n) * 1024), 16, 0, 0);
+        }
+    }
+}
+
+// All of this wave's queued fills have landed in LDS.
+__device__ __forceinline__ void wait_fills() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second:
+// fed two copies of x it leaves {x.lo, x.lo} and {x.hi, x.hi}.  The two results are copied to
+// scalars before the bit cast: a bit cast applied to the vector element directly reads element 0
+// for both with this compiler.
+__device__ __forceinline__ void split_halves(float x, float &lo, float &hi)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const uint32_t r0 = r[0], r1 = r[1];
+    lo = __builtin_bit_cast(float, r0);
+    hi = __builtin_bit_cast(float, r1);
+}
+
+// max over the two 32-lane halves, result in every lane
+__device__ __forceinline__ float max_across_halves(float x)
+{
+    float lo, hi;
+    split_halves(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+
+__device__ __forceinline__ float add_across_halves(float x)
+{
+    float lo, hi;
+    split_halves(x, lo, hi);
+    return lo + hi;
+}
+
 // ============================================================================ forward
-// Workgroup: 4 waves, 128 query rows (32 per wave); keys/values streamed in tiles of 64.
+// Workgroup: 4 waves, 128 query rows (32 per wave); keys/values streamed in tiles of 64 through
+// a double-buffered LDS ring filled asynchronously (one barrier per tile).
 constexpr int kFwdBq = 128, kBk = 64;
 
 __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
 {
-    __shared__ __attribute__((aligned(256))) unsigned char smem[2 * kTileBytes];
-    LDS_AS unsigned char *Ks = (LDS_AS unsigned char *)smem;
-    LDS_AS unsigned char *Vs = Ks + kTileBytes;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes];
+    LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;   // [buf][K|V] tiles
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const LaneAddr la = make_lane_addr(lane);
@@ -193,14 +277,20 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *k = static_cast<const __bf16 *>(a.k) + base;
     const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
+    const TileFill<4> tf = make_tile_fill<4>(wave, lane, a.ss);
+
+    const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
+    const int ntiles = (int)(last_row / kBk) + 1;
+    fill_tile_async(lds, k, a.ss, 0, a.S, tf, wave, lane);
+    fill_tile_async(lds + kTileBytes, v, a.ss, 0, a.S, tf, wave, lane);
 
     // Q^T as B operand: lane = query row i, 8 head-dim values per 16-wide chunk
     bf16x8 qB[8];
+    {
+        const int64_t iq = i < a.S ? i : a.S - 1;     // rows past S are computed and never stored
 #pragma unroll
-    for (int kc = 0; kc < 8; ++kc) {
-        u32x4 raw = {0u, 0u, 0u, 0u};
-        if (i < a.S) raw = *reinterpret_cast<const u32x4 *>(q + i * a.ss + 16 * kc + 8 * half);
-        qB[kc] = __builtin_bit_cast(bf16x8, raw);
+        for (int kc = 0; kc < 8; ++kc)
+            qB[kc] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(q + iq * a.ss + 16 * kc + 8 * half));
     }
 
     f32x16 accO[4];
@@ -208,88 +298,87 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) accO[cb][e] = 0.f;
-    float m = -INFINITY, lsum = 0.f;          // running max of raw dots, running sum (per lane half)
+    float m = -INFINITY, mc = -INFINITY, lsum = 0.f;   // running max of raw dots (and times c), running sum
     const float c = a.scale * kLog2e;
+    const int wave_first_tile_masked = (int)((i0w + 31) / kBk) + 1;   // tiles >= this are fully masked
+    const int wave_first_diag = (int)(i0w / kBk);                     // tiles >= this need the mask
 
-    const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
-    const int64_t ntiles = last_row / kBk + 1;
-
-    RowRegs kreg, vreg;
-    load_rows(kreg, k, a.ss, 0, a.S, tid);
-    load_rows(vreg, v, a.ss, 0, a.S, tid);
-
-    for (int64_t jt = 0; jt < ntiles; ++jt) {
-        const int64_t j0 = jt * kBk;
-        __syncthreads();                      // previous tile fully consumed
-        store_rows(Ks, kreg, tid);
-        store_rows(Vs, vreg, tid);
-        __syncthreads();
+    for (int jt = 0; jt < ntiles; ++jt) {
+        LDS_AS unsigned char *Ks = lds + (jt & 1) * 2 * kTileBytes, *Vs = Ks + kTileBytes;
+        wait_fills();
+        __syncthreads();          // tile jt is complete; nobody still reads the other buffer
         if (jt + 1 < ntiles) {
-            load_rows(kreg, k, a.ss, j0 + kBk, a.S, tid);
-            load_rows(vreg, v, a.ss, j0 + kBk, a.S, tid);
+            LDS_AS unsigned char *Kn = lds + ((jt + 1) & 1) * 2 * kTileBytes;
+            fill_tile_async(Kn, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, tf, wave, lane);
+            fill_tile_async(Kn + kTileBytes, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, tf, wave, lane);
         }
-        if (j0 > i0w + 31) continue;          // every key of this tile is masked for this wave
+        if (jt >= wave_first_tile_masked) continue;   // every key of this tile is masked for this wave
 
         // S^T tile: rows = 64 keys (2 blocks of 32), cols = this wave's 32 queries
         f32x16 s[2];
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb) {
+            bf16x8 ka[8];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) s[jb][e] = 0.f;
+            for (int kc = 0; kc < 8; ++kc) ka[kc] = lds_row_operand(Ks, la.row_op[kc] + jb * 8192);
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            s[jb] = mfma32(ka[0], qB[0], zero);
 #pragma unroll
-            for (int kc = 0; kc < 8; ++kc)
-                s[jb] = mfma32(lds_row_operand(Ks, la.row_op[kc] + jb * 8192), qB[kc], s[jb]);
+            for (int kc = 1; kc < 8; ++kc) s[jb] = mfma32(ka[kc], qB[kc], s[jb]);
         }
-        if (j0 + kBk - 1 > i0w) {             // diagonal tile: mask keys j > i
+        if (jt >= wave_first_diag) {                  // diagonal tile: mask keys j > i
+            const int thr = (int)(i - (int64_t)jt * kBk) - 4 * half;    // key offset e is visible iff e' <= thr
 #pragma unroll
             for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int64_t j = j0 + 32 * jb + 8 * (e >> 2) + 4 * half + (e & 3);
-                    if (j > i) s[jb][e] = -INFINITY;
-                }
+                for (int e = 0; e < 16; ++e)
+                    if (32 * jb + 8 * (e >> 2) + (e & 3) > thr) s[jb][e] = -INFINITY;
         }
-        float mt = s[0][0];
+        float mt = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
+        for (int e = 1; e < 16; ++e) mt = fmaxf(mt, fmaxf(s[0][e], s[1][e]));
+        mt = max_across_halves(mt);
+        // Rescale only when some row of the wave sees a new maximum (rare after the first tiles).
+        // Every processed tile has key j0 visible to all 32 rows, so the maximum is finite.
+        if (__builtin_amdgcn_ballot_w64(mt > m) != 0) {
+            const float m_new = fmaxf(m, mt);
+            const float corr = __builtin_amdgcn_exp2f((m - m_new) * c);
+            m = m_new;
+            mc = m_new * c;
+            lsum *= corr;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) mt = fmaxf(mt, s[jb][e]);
-        mt = fmaxf(mt, __shfl_xor(mt, 32));
-        // every processed tile has j0 <= i for all 32 rows of the wave, so m_new is finite
-        const float m_new = fmaxf(m, mt);
-        const float corr = __builtin_amdgcn_exp2f((m - m_new) * c);
-        const float mc = m_new * c;
-        m = m_new;
-        float psum = 0.f;
+            for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
+                for (int e = 0; e < 16; ++e) accO[cb][e] *= corr;
+        }
+        float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                s[jb][e] = __builtin_amdgcn_exp2f(fmaf(s[jb][e], c, -mc));
-                psum += s[jb][e];
-            }
-        lsum = lsum * corr + psum;
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) accO[cb][e] *= corr;
+        for (int e = 0; e < 16; ++e) {
+            s[0][e] = __builtin_amdgcn_exp2f(fmaf(s[0][e], c, -mc));
+            s[1][e] = __builtin_amdgcn_exp2f(fmaf(s[1][e], c, -mc));
+            psum0 += s[0][e];
+            psum1 += s[1][e];
+        }
+        lsum += psum0 + psum1;
 
         // O^T += V^T P^T : A = V^T (transposed LDS read), B = P^T straight from the score registers
 #pragma unroll
         for (int kj = 0; kj < 4; ++kj) {
+            bf16x8 va[4];
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) va[cb] = lds_tr_operand(Vs, la, cb, kj);
             const bf16x8 pB = pack8(s[kj >> 1], 8 * (kj & 1));
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb)
-                accO[cb] = mfma32(lds_tr_operand(Vs, la, cb, kj), pB, accO[cb]);
+            for (int cb = 0; cb < 4; ++cb) accO[cb] = mfma32(va[cb], pB, accO[cb]);
         }
     }
 
-    const float ltot = lsum + __shfl_xor(lsum, 32);
+    const float ltot = add_across_halves(lsum);
     if (i < a.S) {
         __bf16 *o = static_cast<__bf16 *>(a.o_out) + base + i * a.ss;
         store_acc_T(o, accO, 1.f / ltot, half);
         if (half == 0)
-            a.lse[((int64_t)t.b * a.H + t.h) * a.S + i] = (m * c + __builtin_amdgcn_logf(ltot)) * kLn2;
+            a.lse[((int64_t)t.b * a.H + t.h) * a.S + i] = (mc + __builtin_amdgcn_logf(ltot)) * kLn2;
     }
 }
 
@@ -298,9 +387,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
 //   S^T = K Q^T, dP^T = V dO^T, P = exp(S - LSE), dS = P (dP - D), dQ^T += K^T dS^T
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a)
 {
-    __shared__ __attribute__((aligned(256))) unsigned char smem[2 * kTileBytes];
-    LDS_AS unsigned char *Ks = (LDS_AS unsigned char *)smem;
-    LDS_AS unsigned char *Vs = Ks + kTileBytes;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes];
+    LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;   // [buf][K|V] tiles
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const LaneAddr la = make_lane_addr(lane);
@@ -313,74 +401,79 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a)
     const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
     const int64_t stat = ((int64_t)t.b * a.H + t.h) * a.S;
+    const TileFill<4> tf = make_tile_fill<4>(wave, lane, a.ss);
 
+    const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
+    const int ntiles = (int)(last_row / kBk) + 1;
+    fill_tile_async(lds, k, a.ss, 0, a.S, tf, wave, lane);
+    fill_tile_async(lds + kTileBytes, v, a.ss, 0, a.S, tf, wave, lane);
+
+    const int64_t iq = i < a.S ? i : a.S - 1;         // rows past S are computed and never stored
     bf16x8 qB[8], gB[8];
 #pragma unroll
     for (int kc = 0; kc < 8; ++kc) {
-        u32x4 rq = {0u, 0u, 0u, 0u}, rg = rq;
-        if (i < a.S) {
-            rq = *reinterpret_cast<const u32x4 *>(q + i * a.ss + 16 * kc + 8 * half);
-            rg = *reinterpret_cast<const u32x4 *>(g + i * a.ss + 16 * kc + 8 * half);
-        }
-        qB[kc] = __builtin_bit_cast(bf16x8, rq);
-        gB[kc] = __builtin_bit_cast(bf16x8, rg);
+        qB[kc] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(q + iq * a.ss + 16 * kc + 8 * half));
+        gB[kc] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(g + iq * a.ss + 16 * kc + 8 * half));
     }
     const float c = a.scale * kLog2e;
-    // rows past S: LSE = +inf makes their probabilities exactly zero
-    const float lse2 = (i < a.S) ? a.lse[stat + i] * kLog2e : INFINITY;
-    const float Di = (i < a.S) ? a.delta[stat + i] : 0.f;
+    const float lse2 = a.lse[stat + iq] * kLog2e;
+    const float Di = a.delta[stat + iq];
 
     f32x16 accQ[4];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) accQ[cb][e] = 0.f;
+    const int wave_first_tile_masked = (int)((i0w + 31) / kBk) + 1;
+    const int wave_first_diag = (int)(i0w / kBk);
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
-    const int64_t ntiles = last_row / kBk + 1;
-
-    RowRegs kreg, vreg;
-    load_rows(kreg, k, a.ss, 0, a.S, tid);
-    load_rows(vreg, v, a.ss, 0, a.S, tid);
-
-    for (int64_t jt = 0; jt < ntiles; ++jt) {
-        const int64_t j0 = jt * kBk;
-        __syncthreads();
-        store_rows(Ks, kreg, tid);
-        store_rows(Vs, vreg, tid);
+    for (int jt = 0; jt < ntiles; ++jt) {
+        LDS_AS unsigned char *Ks = lds + (jt & 1) * 2 * kTileBytes, *Vs = Ks + kTileBytes;
+        wait_fills();
         __syncthreads();
         if (jt + 1 < ntiles) {
-            load_rows(kreg, k, a.ss, j0 + kBk, a.S, tid);
-            load_rows(vreg, v, a.ss, j0 + kBk, a.S, tid);
+            LDS_AS unsigned char *Kn = lds + ((jt + 1) & 1) * 2 * kTileBytes;
+            fill_tile_async(Kn, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, tf, wave, lane);
+            fill_tile_async(Kn + kTileBytes, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, tf, wave, lane);
         }
-        if (j0 > i0w + 31) continue;
-        const bool diag = j0 + kBk - 1 > i0w;
-#pragma unroll
+        if (jt >= wave_first_tile_masked) continue;
+        const bool diag = jt >= wave_first_diag;
+        const int thr = (int)(i - (int64_t)jt * kBk) - 4 * half;
+#pragma unroll 1
         for (int jb = 0; jb < 2; ++jb) {
             f32x16 s, dp;
+            {
+                bf16x8 ka[8];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+                for (int kc = 0; kc < 8; ++kc) ka[kc] = lds_row_operand(Ks, la.row_op[kc] + jb * 8192);
+                s = mfma32(ka[0], qB[0], zero);
 #pragma unroll
-            for (int kc = 0; kc < 8; ++kc) {
-                s = mfma32(lds_row_operand(Ks, la.row_op[kc] + jb * 8192), qB[kc], s);
-                dp = mfma32(lds_row_operand(Vs, la.row_op[kc] + jb * 8192), gB[kc], dp);
+                for (int kc = 1; kc < 8; ++kc) s = mfma32(ka[kc], qB[kc], s);
+            }
+            {
+                bf16x8 va[8];
+#pragma unroll
+                for (int kc = 0; kc < 8; ++kc) va[kc] = lds_row_operand(Vs, la.row_op[kc] + jb * 8192);
+                dp = mfma32(va[0], gB[0], zero);
+#pragma unroll
+                for (int kc = 1; kc < 8; ++kc) dp = mfma32(va[kc], gB[kc], dp);
             }
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -lse2));
-                if (diag) {
-                    const int64_t j = j0 + 32 * jb + 8 * (e >> 2) + 4 * half + (e & 3);
-                    if (j > i) p = 0.f;
-                }
+                if (diag && (32 * jb + 8 * (e >> 2) + (e & 3) > thr)) p = 0.f;
                 s[e] = p * (dp[e] - Di);           // dS
             }
             // dQ^T += K^T dS^T : A = K^T (transposed read of the same K tile), B = dS^T registers
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
+                bf16x8 kt[4];
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) kt[cb] = lds_tr_operand(Ks, la, cb, 2 * jb + sub);
                 const bf16x8 dsB = pack8(s, 8 * sub);
 #pragma unroll
-                for (int cb = 0; cb < 4; ++cb)
-                    accQ[cb] = mfma32(lds_tr_operand(Ks, la, cb, 2 * jb + sub), dsB, accQ[cb]);
+                for (int cb = 0; cb < 4; ++cb) accQ[cb] = mfma32(kt[cb], dsB, accQ[cb]);
             }
         }
     }
@@ -391,122 +484,176 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a)
 }
 
 // ============================================================================ backward: dK, dV
-// Workgroup: 4 waves, 128 key rows (32 per wave) held in registers; queries streamed in
-// tiles of 64 from the diagonal to the end of the sequence.
-//   S = Q K^T, dP = dO V^T (key index per lane), P = exp(S - LSE_i), dS = P (dP - D_i),
-//   dV^T += dO^T P, dK^T += Q^T dS      (no atomics: each key row has one owner)
+// Workgroup: 8 waves, 128 key rows; queries streamed in tiles of 64 from the diagonal to the
+// end of the sequence.  Waves w and w+4 form a pair owning key rows 32w..32w+31 and split the
+// four contractions so that each keeps only one 32x128 fp32 accumulator set (two waves per
+// SIMD fit the register file, and the exponentials of one wave overlap the MFMAs of the other):
+//   V-wave (w < 4):  S = Q K^T -> P = exp(S - LSE_i)            | dV^T += dO^T P
+//   K-wave (w >= 4): dP = dO V^T                                 | dS = P (dP - D_i), dK^T += Q^T dS
+// P (fp32) passes from the V-wave to the K-wave through LDS as a register image: both waves
+// hold key j in lane j, so lane l of the K-wave reads back exactly what lane l of the V-wave
+// wrote.  A mid-tile barrier separates the two halves.  No atomics: each key row has one owner.
 constexpr int kBwdBk = 128, kBq = 64;
 
-__global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
+__global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
 {
-    __shared__ __attribute__((aligned(256))) unsigned char smem[2 * kTileBytes + 512];
-    LDS_AS unsigned char *Qs = (LDS_AS unsigned char *)smem;
-    LDS_AS unsigned char *Gs = Qs + kTileBytes;
-    LDS_AS float *Ls = (LDS_AS float *)(Gs + kTileBytes);   // 64 x LSE*log2e
-    LDS_AS float *Ds = Ls + 64;                             // 64 x D_i
+    // [buf][Q|dO] tiles, P exchange (4 pairs x 2 blocks x 64 lanes x 64 B), [buf][LSE*log2e | D] rows
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes + 32768 + 1024];
+    LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
+    LDS_AS unsigned char *Px = lds + 4 * kTileBytes;
+    LDS_AS float *Stat = (LDS_AS float *)(Px + 32768);      // [buf][2][64]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int pair = wave & 3;
+    const bool v_role = wave < 4;
     const LaneAddr la = make_lane_addr(lane);
     const int64_t nkt = (a.S + kBwdBk - 1) / kBwdBk;
     const TileId t = decode_block(a, nkt, false);     // key tile 0 sees every query: heaviest first
-    const int64_t col0 = t.tile * kBwdBk, j0w = col0 + 32 * wave, j = j0w + l32;
+    const int64_t col0 = t.tile * kBwdBk, j0w = col0 + 32 * pair, j = j0w + l32;
     const int64_t base = (int64_t)t.b * a.sb + (int64_t)t.h * a.sh;
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
-    const __bf16 *k = static_cast<const __bf16 *>(a.k) + base;
-    const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
     const int64_t stat = ((int64_t)t.b * a.H + t.h) * a.S;
+    const TileFill<8> tf = make_tile_fill<8>(wave, lane, a.ss);
 
-    bf16x8 kB[8], vB[8];
+    const int it0 = (int)(col0 / kBq);
+    const int nit = (int)((a.S + kBq - 1) / kBq);
+    fill_tile_async(lds, q, a.ss, (int64_t)it0 * kBq, a.S, tf, wave, lane);
+    fill_tile_async(lds + kTileBytes, g, a.ss, (int64_t)it0 * kBq, a.S, tf, wave, lane);
+
+    // this wave's resident B operand: K rows (V-wave) or V rows (K-wave); lane = key j
+    bf16x8 wB[8];
+    {
+        const __bf16 *src = static_cast<const __bf16 *>(v_role ? a.k : a.v) + base;
+        const int64_t jq = j < a.S ? j : a.S - 1;     // keys past S are computed and never stored
 #pragma unroll
-    for (int kc = 0; kc < 8; ++kc) {
-        u32x4 rk = {0u, 0u, 0u, 0u}, rv = rk;
-        if (j < a.S) {
-            rk = *reinterpret_cast<const u32x4 *>(k + j * a.ss + 16 * kc + 8 * half);
-            rv = *reinterpret_cast<const u32x4 *>(v + j * a.ss + 16 * kc + 8 * half);
-        }
-        kB[kc] = __builtin_bit_cast(bf16x8, rk);
-        vB[kc] = __builtin_bit_cast(bf16x8, rv);
+        for (int kc = 0; kc < 8; ++kc)
+            wB[kc] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(src + jq * a.ss + 16 * kc + 8 * half));
     }
     const float c = a.scale * kLog2e;
-
-    f32x16 accK[4], accV[4];
+    f32x16 acc[4];                                    // dV^T (V-wave) or dK^T (K-wave)
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { accK[cb][e] = 0.f; accV[cb][e] = 0.f; }
+        for (int e = 0; e < 16; ++e) acc[cb][e] = 0.f;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    const int64_t it0 = col0 / kBq;
-    const int64_t nit = (a.S + kBq - 1) / kBq;
-
-    RowRegs qreg, greg;
-    float lreg = 0.f, dreg = 0.f;
-    auto fetch = [&](int64_t i0) {
-        load_rows(qreg, q, a.ss, i0, a.S, tid);
-        load_rows(greg, g, a.ss, i0, a.S, tid);
-        if (tid < 64) {
-            const bool ok = i0 + tid < a.S;
-            // rows past S: LSE = +inf makes their probabilities exactly zero
-            lreg = ok ? a.lse[stat + i0 + tid] * kLog2e : INFINITY;
-            dreg = ok ? a.delta[stat + i0 + tid] : 0.f;
-        }
+    // per-row statistics of a query tile: threads 0..63 LSE*log2e, threads 64..127 D_i.
+    // rows past S: LSE = +inf makes their probabilities exactly zero
+    auto load_stat = [&](int it) -> float {
+        if (tid >= 128) return 0.f;
+        const int64_t r = (int64_t)it * kBq + (tid & 63);
+        if (tid < 64) return r < a.S ? a.lse[stat + r] * kLog2e : INFINITY;
+        return r < a.S ? a.delta[stat + r] : 0.f;
     };
-    fetch(it0 * kBq);
+    float sreg = load_stat(it0);
+    if (tid < 128) Stat[tid] = sreg;
+    LDS_AS unsigned char *Pw = Px + pair * 8192 + lane * 16;   // + ib*4096 + 1024*(e/4)
 
-    for (int64_t it = it0; it < nit; ++it) {
-        const int64_t i0 = it * kBq;
-        __syncthreads();
-        store_rows(Qs, qreg, tid);
-        store_rows(Gs, greg, tid);
-        if (tid < 64) { Ls[tid] = lreg; Ds[tid] = dreg; }
-        __syncthreads();
-        if (it + 1 < nit) fetch(i0 + kBq);
-        if (i0 + kBq - 1 < j0w) continue;       // all 64 queries precede this wave's keys
+    for (int it = it0; it < nit; ++it) {
+        const int cur = (it - it0) & 1;
+        LDS_AS unsigned char *Qs = lds + cur * 2 * kTileBytes, *Gs = Qs + kTileBytes;
+        const LDS_AS float *Ls = Stat + cur * 128, *Ds = Ls + 64;
+        wait_fills();
+        __syncthreads();          // tile `it` and its statistics are complete; the other buffers are free
+        if (it + 1 < nit) {
+            LDS_AS unsigned char *Qn = lds + (cur ^ 1) * 2 * kTileBytes;
+            fill_tile_async(Qn, q, a.ss, (int64_t)(it + 1) * kBq, a.S, tf, wave, lane);
+            fill_tile_async(Qn + kTileBytes, g, a.ss, (int64_t)(it + 1) * kBq, a.S, tf, wave, lane);
+            sreg = load_stat(it + 1);
+        }
+        const int64_t i0 = (int64_t)it * kBq;
+        const bool active = i0 + kBq - 1 >= j0w;      // else all 64 queries precede this pair's keys
         const bool diag = i0 < j0w + 31;
+        const int thr = (int)(j - i0) - 4 * half;     // query offset e' is visible iff e' >= thr
+        bf16x8 pB[4];                                 // V-wave: P chunks [2*ib + sub]
+        f32x16 dp[2];                                 // K-wave: dP blocks
+
+        // ---- first half: scores and probabilities (V-wave), dP (K-wave)
+        if (active) {
+            if (v_role) {
 #pragma unroll
-        for (int ib = 0; ib < 2; ++ib) {
-            f32x16 s, dp;
+                for (int ib = 0; ib < 2; ++ib) {
+                    bf16x8 qa[8];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+                    for (int kc = 0; kc < 8; ++kc) qa[kc] = lds_row_operand(Qs, la.row_op[kc] + ib * 8192);
+                    f32x16 s = mfma32(qa[0], wB[0], zero);
 #pragma unroll
-            for (int kc = 0; kc < 8; ++kc) {
-                s = mfma32(lds_row_operand(Qs, la.row_op[kc] + ib * 8192), kB[kc], s);
-                dp = mfma32(lds_row_operand(Gs, la.row_op[kc] + ib * 8192), vB[kc], dp);
-            }
-            // s, dp: lane = key j, register e = query row 32*ib + 8*(e/4) + 4*half + e%4
+                    for (int kc = 1; kc < 8; ++kc) s = mfma32(qa[kc], wB[kc], s);
+                    // s: lane = key j, register e = query row 32*ib + 8*(e/4) + 4*half + e%4
 #pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * ib + 8 * gq + 4 * half);
-                const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * ib + 8 * gq + 4 * half);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-                const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * ib + 8 * gq + 4 * half);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int e = 4 * gq + r;
-                    float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -lv[r]));
-                    if (diag) {
-                        const int64_t ii = i0 + 32 * ib + 8 * gq + 4 * half + r;
-                        if (ii < j) p = 0.f;
+                        for (int r = 0; r < 4; ++r) {
+                            const int e = 4 * gq + r;
+                            float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[r]));
+                            if (diag && (32 * ib + 8 * gq + r < thr)) p = 0.f;
+                            s[e] = p;
+                        }
                     }
-                    s[e] = p;
-                    dp[e] = p * (dp[e] - dl[r]);    // dS
+                    pB[2 * ib] = pack8(s, 0);
+                    pB[2 * ib + 1] = pack8(s, 8);
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const f32x4 p4 = {s[4 * gq], s[4 * gq + 1], s[4 * gq + 2], s[4 * gq + 3]};
+                        *reinterpret_cast<LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024) = p4;
+                    }
                 }
-            }
+            } else {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                const bf16x8 pB = pack8(s, 8 * sub);
-                const bf16x8 dsB = pack8(dp, 8 * sub);
+                for (int ib = 0; ib < 2; ++ib) {
+                    bf16x8 ga[8];
 #pragma unroll
-                for (int cb = 0; cb < 4; ++cb) {
-                    accV[cb] = mfma32(lds_tr_operand(Gs, la, cb, 2 * ib + sub), pB, accV[cb]);
-                    accK[cb] = mfma32(lds_tr_operand(Qs, la, cb, 2 * ib + sub), dsB, accK[cb]);
+                    for (int kc = 0; kc < 8; ++kc) ga[kc] = lds_row_operand(Gs, la.row_op[kc] + ib * 8192);
+                    dp[ib] = mfma32(ga[0], wB[0], zero);
+#pragma unroll
+                    for (int kc = 1; kc < 8; ++kc) dp[ib] = mfma32(ga[kc], wB[kc], dp[ib]);
                 }
             }
         }
+        __syncthreads();          // P of this tile is in LDS
+        // ---- second half: dV (V-wave), dS and dK (K-wave)
+        if (active) {
+            if (v_role) {
+#pragma unroll
+                for (int qi = 0; qi < 4; ++qi) {
+                    bf16x8 gt[4];
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) gt[cb] = lds_tr_operand(Gs, la, cb, qi);
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) acc[cb] = mfma32(gt[cb], pB[qi], acc[cb]);
+                }
+            } else {
+#pragma unroll
+                for (int ib = 0; ib < 2; ++ib) {
+#pragma unroll
+                    for (int sub = 0; sub < 2; ++sub) {
+                        f32x16 ds;
+#pragma unroll
+                        for (int gg = 0; gg < 2; ++gg) {
+                            // registers 8*sub + 4*gg + r of the block = query rows 16*sub + 8*gg + 4*half + r
+                            const int gq = 2 * sub + gg;
+                            const f32x4 p4 = *reinterpret_cast<const LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024);
+                            const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * ib + 8 * gq + 4 * half);
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) ds[4 * gg + r] = p4[r] * (dp[ib][4 * gq + r] - d4[r]);
+                        }
+                        bf16x8 qt[4];
+#pragma unroll
+                        for (int cb = 0; cb < 4; ++cb) qt[cb] = lds_tr_operand(Qs, la, cb, 2 * ib + sub);
+                        const bf16x8 dsB = pack8(ds, 0);
+#pragma unroll
+                        for (int cb = 0; cb < 4; ++cb) acc[cb] = mfma32(qt[cb], dsB, acc[cb]);
+                    }
+                }
+            }
+        }
+        if (it + 1 < nit && tid < 128) Stat[(cur ^ 1) * 128 + tid] = sreg;
     }
     if (j < a.S) {
-        store_acc_T(static_cast<__bf16 *>(a.dk) + base + j * a.ss, accK, a.scale, half);
-        store_acc_T(static_cast<__bf16 *>(a.dv) + base + j * a.ss, accV, 1.f, half);
+        __bf16 *out = static_cast<__bf16 *>(v_role ? a.dv : a.dk) + base + j * a.ss;
+        store_acc_T(out, acc, v_role ? 1.f : a.scale, half);
     }
 }
 
@@ -530,7 +677,7 @@ hipError_t launch_attn_bwd_bf16(const AttnArgs &a, hipStream_t st)
     if (e != hipSuccess) return e;
     if ((e = launch_attn_delta(a, true, st)) != hipSuccess) return e;
     if ((e = record_stage(a, 1, st)) != hipSuccess) return e;
-    attn_bwd_dkdv_bf16_kernel<<<dim3((unsigned)(nkt * a.H * a.B)), 256, 0, st>>>(a);
+    attn_bwd_dkdv_bf16_kernel<<<dim3((unsigned)(nkt * a.H * a.B)), 512, 0, st>>>(a);
     if ((e = record_stage(a, 2, st)) != hipSuccess) return e;
     attn_bwd_dq_bf16_kernel<<<dim3((unsigned)(nqt * a.H * a.B)), 256, 0, st>>>(a);
     if ((e = record_stage(a, 3, st)) != hipSuccess) return e;

@@ -5,10 +5,11 @@ import torch
 from paper_2407_12117_amd import binding as mb
 
 # Parity bars.  bf16: outputs and gradients within max-abs 2e-2 and relative-L2 1e-2 of the
-# fp64 oracle; fp32 path within 1e-4; logsumexp is an fp32 output on both paths.
+# fp64 oracle; fp32 path within 1e-4.  The logsumexp is an fp32 output on both paths (bf16
+# inputs are exact in fp32, products accumulate in fp32), so it gets a much tighter bar.
 BF16_MAX_ABS, BF16_REL_L2 = 2e-2, 1e-2
 F32_MAX_ABS = 1e-4
-LSE_MAX_ABS_BF16 = 2e-3
+LSE_MAX_ABS_BF16 = 1e-4
 
 
 def to_f64(t):
