@@ -177,42 +177,44 @@ __device__ __forceinline__ TileId decode_block(const AttnArgs &a, int64_t ntiles
 
 // ---- asynchronous tile fill: global -> LDS without passing through registers -------------
 // One global_load_lds_dwordx4 moves 64 x 16 bytes: lane l lands at LDS base + 16*l, i.e. four
-// tile rows of sixteen chunks.  Wave w issues instruction n for tile rows 16w + 4n + l/16; the
-// lane at chunk position p = l%16 fetches logical chunk p ^ swz(row), so the swizzle is applied
-// on the global side.  Offsets are 32-bit from a wave-uniform tile base (scalar base + vector
-// offset addressing): no per-tile vector address arithmetic.
-template <int NW>      // NW waves share the 16 fill instructions of a 64-row tile
-struct TileFill {
+// tile rows of sixteen chunks.  With NW waves sharing a tile, wave w issues instruction n for
+// tile rows 4*(NI*w + n) + l/16 (NI = 16/NW); the lane at chunk position p = l%16 fetches
+// logical chunk p ^ swz(row), so the swizzle is applied on the global side.  Each lane keeps
+// the global address of its piece per instruction and steps it by one tile (a wave-uniform
+// stride) after every fill: one 64-bit add per instruction and tile, nothing else.
+template <int NW>
+struct TileStream {
     static constexpr int kInstr = 16 / NW;
-    uint32_t goff[16 / NW];   // byte offset of this lane's 16 bytes from the tile's first row, per n
+    const char *p[16 / NW];
 };
 
 template <int NW>
-__device__ __forceinline__ TileFill<NW> make_tile_fill(int wave, int lane, int64_t ss)
+__device__ __forceinline__ TileStream<NW> make_tile_stream(const __bf16 *src, int64_t ss, int64_t r0,
+                                                           int wave, int lane)
 {
-    TileFill<NW> f;
+    TileStream<NW> f;
 #pragma unroll
-    for (int n = 0; n < TileFill<NW>::kInstr; ++n) {
-        const int row = 4 * (TileFill<NW>::kInstr * wave + n) + (lane >> 4);
+    for (int n = 0; n < TileStream<NW>::kInstr; ++n) {
+        const int row = 4 * (TileStream<NW>::kInstr * wave + n) + (lane >> 4);
         const int chunk = (lane & 15) ^ swz(row);
-        f.goff[n] = (uint32_t)((row * ss + chunk * 8) * 2);
+        f.p[n] = reinterpret_cast<const char *>(src + (r0 + row) * ss + chunk * 8);
     }
     return f;
 }
 
-// Queues the fill of one 64-row tile starting at row r0 of the head view `src`.  Rows past S
-// re-read row S-1 (finite values; every consumer masks them).  r0, S, src are wave-uniform.
+// Queues the fill of the 64-row tile the stream points at (rows r0..r0+63 of the head view
+// `src`) and steps the stream to the next tile.  A tile that reaches past row S-1 takes the
+// slow path: rows past S re-read row S-1 (finite values; every consumer masks them).
 template <int NW>
-__device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, const __bf16 *src, int64_t ss,
-                                                int64_t r0, int64_t S, const TileFill<NW> &f, int wave,
-                                                int lane)
+__device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, TileStream<NW> &f,
+                                                const __bf16 *src, int64_t ss, int64_t r0, int64_t S,
+                                                int wave, int lane)
 {
-    constexpr int NI = TileFill<NW>::kInstr;
-    if (r0 + 64 <= S) {
-        const char *tb = reinterpret_cast<const char *>(src + r0 * ss);
+    constexpr int NI = TileStream<NW>::kInstr;
+    if (__builtin_expect(r0 + 64 <= S, 1)) {
 #pragma unroll
         for (int n = 0; n < NI; ++n)
-            __builtin_amdgcn_global_load_lds((const GLB_AS void *)(tb + f.goff[n]),
+            __builtin_amdgcn_global_load_lds((const GLB_AS void *)f.p[n],
                                              (LDS_AS void *)(tile + (NI * wave + n) * 1024), 16, 0, 0);
     } else {
 #pragma unroll
@@ -225,6 +227,9 @@ __device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, cons
                                              (LDS_AS void *)(tile + (NI * wave + n) * 1024), 16, 0, 0);
         }
     }
+    const int64_t step = 64 * ss * 2;
+#pragma unroll
+    for (int n = 0; n < NI; ++n) f.p[n] += step;
 }
 
 // All of this wave's queued fills have landed in LDS.
@@ -263,6 +268,8 @@ __device__ __forceinline__ float add_across_halves(float x)
 // a double-buffered LDS ring filled asynchronously (one barrier per tile).
 constexpr int kFwdBq = 128, kBk = 64;
 
+template <int N> struct IntC { static constexpr int value = N; };
+
 __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes];
@@ -277,12 +284,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *k = static_cast<const __bf16 *>(a.k) + base;
     const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
-    const TileFill<4> tf = make_tile_fill<4>(wave, lane, a.ss);
+    TileStream<4> ks = make_tile_stream<4>(k, a.ss, 0, wave, lane);
+    TileStream<4> vs = make_tile_stream<4>(v, a.ss, 0, wave, lane);
 
     const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
     const int ntiles = (int)(last_row / kBk) + 1;
-    fill_tile_async(lds, k, a.ss, 0, a.S, tf, wave, lane);
-    fill_tile_async(lds + kTileBytes, v, a.ss, 0, a.S, tf, wave, lane);
+    fill_tile_async(lds, ks, k, a.ss, 0, a.S, wave, lane);
+    fill_tile_async(lds + kTileBytes, vs, v, a.ss, 0, a.S, wave, lane);
 
     // Q^T as B operand: lane = query row i, 8 head-dim values per 16-wide chunk
     bf16x8 qB[8];
@@ -302,17 +310,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
     const float c = a.scale * kLog2e;
     const int wave_first_tile_masked = (int)((i0w + 31) / kBk) + 1;   // tiles >= this are fully masked
     const int wave_first_diag = (int)(i0w / kBk);                     // tiles >= this need the mask
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    for (int jt = 0; jt < ntiles; ++jt) {
-        LDS_AS unsigned char *Ks = lds + (jt & 1) * 2 * kTileBytes, *Vs = Ks + kTileBytes;
+    // One key/value tile.  BUF is a compile-time buffer index, so every LDS address below is
+    // a per-lane register plus an immediate offset.
+    auto tile_step = [&](auto bufc, int jt) {
+        constexpr int BUF = decltype(bufc)::value;
+        constexpr int kOff = BUF * 2 * kTileBytes, vOff = kOff + kTileBytes;
+        constexpr int nOff = (BUF ^ 1) * 2 * kTileBytes;
         wait_fills();
         __syncthreads();          // tile jt is complete; nobody still reads the other buffer
         if (jt + 1 < ntiles) {
-            LDS_AS unsigned char *Kn = lds + ((jt + 1) & 1) * 2 * kTileBytes;
-            fill_tile_async(Kn, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, tf, wave, lane);
-            fill_tile_async(Kn + kTileBytes, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, tf, wave, lane);
+            fill_tile_async(lds + nOff, ks, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
+            fill_tile_async(lds + nOff + kTileBytes, vs, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
         }
-        if (jt >= wave_first_tile_masked) continue;   // every key of this tile is masked for this wave
+        if (jt >= wave_first_tile_masked) return;     // every key of this tile is masked for this wave
 
         // S^T tile: rows = 64 keys (2 blocks of 32), cols = this wave's 32 queries
         f32x16 s[2];
@@ -320,14 +332,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
         for (int jb = 0; jb < 2; ++jb) {
             bf16x8 ka[8];
 #pragma unroll
-            for (int kc = 0; kc < 8; ++kc) ka[kc] = lds_row_operand(Ks, la.row_op[kc] + jb * 8192);
-            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int kc = 0; kc < 8; ++kc) ka[kc] = lds_row_operand(lds, la.row_op[kc] + jb * 8192 + kOff);
             s[jb] = mfma32(ka[0], qB[0], zero);
 #pragma unroll
             for (int kc = 1; kc < 8; ++kc) s[jb] = mfma32(ka[kc], qB[kc], s[jb]);
         }
         if (jt >= wave_first_diag) {                  // diagonal tile: mask keys j > i
-            const int thr = (int)(i - (int64_t)jt * kBk) - 4 * half;    // key offset e is visible iff e' <= thr
+            const int thr = (int)(i - (int64_t)jt * kBk) - 4 * half;    // key offset e' is visible iff e' <= thr
 #pragma unroll
             for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
@@ -366,11 +377,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
         for (int kj = 0; kj < 4; ++kj) {
             bf16x8 va[4];
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb) va[cb] = lds_tr_operand(Vs, la, cb, kj);
+            for (int cb = 0; cb < 4; ++cb) va[cb] = lds_tr_operand(lds + vOff, la, cb, kj);
             const bf16x8 pB = pack8(s[kj >> 1], 8 * (kj & 1));
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb) accO[cb] = mfma32(va[cb], pB, accO[cb]);
         }
+    };
+
+    for (int jt = 0; jt < ntiles; jt += 2) {
+        tile_step(IntC<0>{}, jt);
+        if (jt + 1 < ntiles) tile_step(IntC<1>{}, jt + 1);
     }
 
     const float ltot = add_across_halves(lsum);
@@ -401,12 +417,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a)
     const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
     const int64_t stat = ((int64_t)t.b * a.H + t.h) * a.S;
-    const TileFill<4> tf = make_tile_fill<4>(wave, lane, a.ss);
+    TileStream<4> ks = make_tile_stream<4>(k, a.ss, 0, wave, lane);
+    TileStream<4> vs = make_tile_stream<4>(v, a.ss, 0, wave, lane);
 
     const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
     const int ntiles = (int)(last_row / kBk) + 1;
-    fill_tile_async(lds, k, a.ss, 0, a.S, tf, wave, lane);
-    fill_tile_async(lds + kTileBytes, v, a.ss, 0, a.S, tf, wave, lane);
+    fill_tile_async(lds, ks, k, a.ss, 0, a.S, wave, lane);
+    fill_tile_async(lds + kTileBytes, vs, v, a.ss, 0, a.S, wave, lane);
 
     const int64_t iq = i < a.S ? i : a.S - 1;         // rows past S are computed and never stored
     bf16x8 qB[8], gB[8];
@@ -434,8 +451,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a)
         __syncthreads();
         if (jt + 1 < ntiles) {
             LDS_AS unsigned char *Kn = lds + ((jt + 1) & 1) * 2 * kTileBytes;
-            fill_tile_async(Kn, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, tf, wave, lane);
-            fill_tile_async(Kn + kTileBytes, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, tf, wave, lane);
+            fill_tile_async(Kn, ks, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
+            fill_tile_async(Kn + kTileBytes, vs, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
         }
         if (jt >= wave_first_tile_masked) continue;
         const bool diag = jt >= wave_first_diag;
@@ -514,12 +531,13 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
     const int64_t stat = ((int64_t)t.b * a.H + t.h) * a.S;
-    const TileFill<8> tf = make_tile_fill<8>(wave, lane, a.ss);
 
     const int it0 = (int)(col0 / kBq);
     const int nit = (int)((a.S + kBq - 1) / kBq);
-    fill_tile_async(lds, q, a.ss, (int64_t)it0 * kBq, a.S, tf, wave, lane);
-    fill_tile_async(lds + kTileBytes, g, a.ss, (int64_t)it0 * kBq, a.S, tf, wave, lane);
+    TileStream<8> qs = make_tile_stream<8>(q, a.ss, (int64_t)it0 * kBq, wave, lane);
+    TileStream<8> gs = make_tile_stream<8>(g, a.ss, (int64_t)it0 * kBq, wave, lane);
+    fill_tile_async(lds, qs, q, a.ss, (int64_t)it0 * kBq, a.S, wave, lane);
+    fill_tile_async(lds + kTileBytes, gs, g, a.ss, (int64_t)it0 * kBq, a.S, wave, lane);
 
     // this wave's resident B operand: K rows (V-wave) or V rows (K-wave); lane = key j
     bf16x8 wB[8];
@@ -558,8 +576,8 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
         __syncthreads();          // tile `it` and its statistics are complete; the other buffers are free
         if (it + 1 < nit) {
             LDS_AS unsigned char *Qn = lds + (cur ^ 1) * 2 * kTileBytes;
-            fill_tile_async(Qn, q, a.ss, (int64_t)(it + 1) * kBq, a.S, tf, wave, lane);
-            fill_tile_async(Qn + kTileBytes, g, a.ss, (int64_t)(it + 1) * kBq, a.S, tf, wave, lane);
+            fill_tile_async(Qn, qs, q, a.ss, (int64_t)(it + 1) * kBq, a.S, wave, lane);
+            fill_tile_async(Qn + kTileBytes, gs, g, a.ss, (int64_t)(it + 1) * kBq, a.S, wave, lane);
             sreg = load_stat(it + 1);
         }
         const int64_t i0 = (int64_t)it * kBq;
