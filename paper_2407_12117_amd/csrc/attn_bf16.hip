@@ -84,6 +84,21 @@ __device__ __forceinline__ LaneAddr make_lane_addr(int lane)
     return la;
 }
 
+// the same offsets as absolute LDS byte addresses (for the hand-issued reads)
+struct LdsAddr { uint32_t row[8]; uint32_t tr[4][2]; };
+__device__ __forceinline__ LdsAddr make_lds_addr(const LDS_AS unsigned char *base, const LaneAddr &la)
+{
+    LdsAddr ad;
+    const uint32_t b = (uint32_t)(uintptr_t)base;
+#pragma unroll
+    for (int kc = 0; kc < 8; ++kc) ad.row[kc] = b + (uint32_t)la.row_op[kc];
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int sec = 0; sec < 2; ++sec) ad.tr[cb][sec] = b + (uint32_t)la.tr_op[cb][sec];
+    return ad;
+}
+
 __device__ __forceinline__ bf16x8 lds_row_operand(const LDS_AS unsigned char *tile, int off)
 {
     return *reinterpret_cast<const LDS_AS bf16x8 *>(tile + off);
@@ -232,6 +247,86 @@ __device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, Tile
     for (int n = 0; n < NI; ++n) f.p[n] += step;
 }
 
+// ---- software-pipelined LDS operand reads ---------------------------------------------------
+// The compiler issues an LDS read right before the MFMA that consumes it and then waits for ALL
+// outstanding LDS traffic, which exposes the full LDS latency once per MFMA.  The operand reads of
+// the contractions are therefore issued by hand, several MFMAs ahead, through a small ring of
+// registers, and each MFMA waits only until its own operand has landed.  LDS returns data in
+// issue order, so "at most N reads still outstanding" (s_waitcnt lgkmcnt(N)) means that every
+// read issued before the last N has completed; N counts only reads issued through these helpers
+// after the wanted one, so any other LDS traffic in between can only make a wait longer, never
+// too short.  The wait names the registers it guards as in/out operands, which orders it before
+// their first use.
+template <int N> struct IntC { static constexpr int value = N; };
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(IntC<I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+struct TrSlot { s16x4 lo, hi; };      // the two halves of a transposed operand
+
+template <int OFF>
+__device__ __forceinline__ void lds_issue_b128(bf16x8 &dst, uint32_t addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "LDS immediate offset");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+
+template <int OFF>
+__device__ __forceinline__ void lds_issue_tr(TrSlot &dst, uint32_t addr_lo, uint32_t addr_hi)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "LDS immediate offset");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst.lo) : "v"(addr_lo), "n"(OFF) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst.hi) : "v"(addr_hi), "n"(OFF) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void lds_wait(bf16x8 &x)
+{
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
+}
+
+template <int N>
+__device__ __forceinline__ void lds_wait(TrSlot &x)
+{
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x.lo), "+v"(x.hi) : "n"(N));
+}
+
+__device__ __forceinline__ bf16x8 tr_operand(const TrSlot &t)
+{
+    const s16x8 both = __builtin_shufflevector(t.lo, t.hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+
+// Runs items 0..N-1; item n's operand is read DEPTH items ahead of its use.  RPI = LDS reads per
+// item (1 for a row operand, 2 for a transposed one).  issue(IntC<n>, slot&), use(IntC<n>, slot&).
+// `ring` holds DEPTH+1 slots; the first `PRE` items may have been issued earlier by
+// lds_pipeline_prologue (with nothing but other reads of these helpers in between).
+template <int N, int DEPTH, int RPI, typename Slot, typename Issue>
+__device__ __forceinline__ void lds_pipeline_prologue(Slot (&ring)[DEPTH + 1], Issue &&issue)
+{
+    static_for<0, (DEPTH < N ? DEPTH : N)>([&](auto n) { issue(n, ring[decltype(n)::value % (DEPTH + 1)]); });
+}
+
+template <int N, int DEPTH, int RPI, typename Slot, typename Issue, typename Use>
+__device__ __forceinline__ void lds_pipeline_body(Slot (&ring)[DEPTH + 1], Issue &&issue, Use &&use)
+{
+    static_for<0, N>([&](auto n) {
+        constexpr int i = decltype(n)::value;
+        if constexpr (i + DEPTH < N) issue(IntC<i + DEPTH>{}, ring[(i + DEPTH) % (DEPTH + 1)]);
+        constexpr int later = (i + DEPTH < N ? DEPTH : N - 1 - i) * RPI;
+        lds_wait<later>(ring[i % (DEPTH + 1)]);
+        use(n, ring[i % (DEPTH + 1)]);
+    });
+}
+
 // All of this wave's queued fills have landed in LDS.
 __device__ __forceinline__ void wait_fills() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -264,18 +359,19 @@ __device__ __forceinline__ float add_across_halves(float x)
 }
 
 // ============================================================================ forward
-// Workgroup: 4 waves, 128 query rows (32 per wave); keys/values streamed in tiles of 64 through
-// a double-buffered LDS ring filled asynchronously (one barrier per tile).
-constexpr int kFwdBq = 128, kBk = 64;
+// Workgroup: kFwdWaves waves, 32 query rows per wave; keys/values streamed in tiles of 64 through
+// a double-buffered LDS ring filled asynchronously (one barrier per tile).  The more query rows
+// share a K/V tile, the less fill traffic (L2 -> LDS) each MFMA has to pay for.
+constexpr int kFwdWaves = 8;                 // waves per workgroup in the forward and dQ kernels
+constexpr int kFwdBq = 32 * kFwdWaves, kBk = 64;
 
-template <int N> struct IntC { static constexpr int value = N; };
-
-__global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
+__global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs a)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;   // [buf][K|V] tiles
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
     const LaneAddr la = make_lane_addr(lane);
     const int64_t nqt = (a.S + kFwdBq - 1) / kFwdBq;
     const TileId t = decode_block(a, nqt, true);      // heaviest query tiles first
@@ -284,8 +380,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *k = static_cast<const __bf16 *>(a.k) + base;
     const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
-    TileStream<4> ks = make_tile_stream<4>(k, a.ss, 0, wave, lane);
-    TileStream<4> vs = make_tile_stream<4>(v, a.ss, 0, wave, lane);
+    TileStream<kFwdWaves> ks = make_tile_stream<kFwdWaves>(k, a.ss, 0, wave, lane);
+    TileStream<kFwdWaves> vs = make_tile_stream<kFwdWaves>(v, a.ss, 0, wave, lane);
 
     const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
     const int ntiles = (int)(last_row / kBk) + 1;
@@ -311,6 +407,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
     const int wave_first_tile_masked = (int)((i0w + 31) / kBk) + 1;   // tiles >= this are fully masked
     const int wave_first_diag = (int)(i0w / kBk);                     // tiles >= this need the mask
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const LdsAddr ad = make_lds_addr(lds, la);
+    const uint32_t (&row_addr)[8] = ad.row;
+    const uint32_t (&tr_addr)[4][2] = ad.tr;
 
     // One key/value tile.  BUF is a compile-time buffer index, so every LDS address below is
     // a per-lane register plus an immediate offset.
@@ -326,17 +425,28 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
         }
         if (jt >= wave_first_tile_masked) return;     // every key of this tile is masked for this wave
 
-        // S^T tile: rows = 64 keys (2 blocks of 32), cols = this wave's 32 queries
+        // S^T tile: rows = 64 keys (2 blocks of 32), cols = this wave's 32 queries.
+        // item n = (jb = n/8, kc = n%8): one row operand of K, read 4 MFMAs ahead
         f32x16 s[2];
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
-            bf16x8 ka[8];
-#pragma unroll
-            for (int kc = 0; kc < 8; ++kc) ka[kc] = lds_row_operand(lds, la.row_op[kc] + jb * 8192 + kOff);
-            s[jb] = mfma32(ka[0], qB[0], zero);
-#pragma unroll
-            for (int kc = 1; kc < 8; ++kc) s[jb] = mfma32(ka[kc], qB[kc], s[jb]);
+        {
+            bf16x8 ring[5];
+            auto issue = [&](auto n, bf16x8 &slot) {
+                constexpr int jb = decltype(n)::value / 8, kc = decltype(n)::value % 8;
+                lds_issue_b128<jb * 8192 + kOff>(slot, row_addr[kc]);
+            };
+            lds_pipeline_prologue<16, 4, 1>(ring, issue);
+            lds_pipeline_body<16, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
+                constexpr int jb = decltype(n)::value / 8, kc = decltype(n)::value % 8;
+                s[jb] = mfma32(slot, qB[kc], kc == 0 ? zero : s[jb]);
+            });
         }
+        // the first V^T operands are requested now: their latency hides behind the softmax
+        TrSlot vring[4];
+        auto v_issue = [&](auto n, TrSlot &slot) {
+            constexpr int kj = decltype(n)::value / 4, cb = decltype(n)::value % 4;
+            lds_issue_tr<kj * 4096 + vOff>(slot, tr_addr[cb][0], tr_addr[cb][1]);
+        };
+        lds_pipeline_prologue<16, 3, 2>(vring, v_issue);
         if (jt >= wave_first_diag) {                  // diagonal tile: mask keys j > i
             const int thr = (int)(i - (int64_t)jt * kBk) - 4 * half;    // key offset e' is visible iff e' <= thr
 #pragma unroll
@@ -372,16 +482,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
         }
         lsum += psum0 + psum1;
 
-        // O^T += V^T P^T : A = V^T (transposed LDS read), B = P^T straight from the score registers
+        // O^T += V^T P^T : A = V^T (transposed LDS read), B = P^T straight from the score registers.
+        // item n = (kj = n/4, cb = n%4)
+        bf16x8 pB[4];
 #pragma unroll
-        for (int kj = 0; kj < 4; ++kj) {
-            bf16x8 va[4];
-#pragma unroll
-            for (int cb = 0; cb < 4; ++cb) va[cb] = lds_tr_operand(lds + vOff, la, cb, kj);
-            const bf16x8 pB = pack8(s[kj >> 1], 8 * (kj & 1));
-#pragma unroll
-            for (int cb = 0; cb < 4; ++cb) accO[cb] = mfma32(va[cb], pB, accO[cb]);
-        }
+        for (int kj = 0; kj < 4; ++kj) pB[kj] = pack8(s[kj >> 1], 8 * (kj & 1));
+        lds_pipeline_body<16, 3, 2>(vring, v_issue, [&](auto n, TrSlot &slot) {
+            constexpr int kj = decltype(n)::value / 4, cb = decltype(n)::value % 4;
+            accO[cb] = mfma32(tr_operand(slot), pB[kj], accO[cb]);
+        });
     };
 
     for (int jt = 0; jt < ntiles; jt += 2) {
@@ -399,14 +508,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a)
 }
 
 // ============================================================================ backward: dQ
-// Same shape as the forward: 128 query rows per workgroup, keys/values streamed.
+// Same shape as the forward: 32 query rows per wave, keys/values streamed.
 //   S^T = K Q^T, dP^T = V dO^T, P = exp(S - LSE), dS = P (dP - D), dQ^T += K^T dS^T
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a)
+__global__ __launch_bounds__(64 * kFwdWaves) void attn_bwd_dq_bf16_kernel(AttnArgs a)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;   // [buf][K|V] tiles
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
     const LaneAddr la = make_lane_addr(lane);
     const int64_t nqt = (a.S + kFwdBq - 1) / kFwdBq;
     const TileId t = decode_block(a, nqt, true);
@@ -417,8 +527,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a)
     const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
     const int64_t stat = ((int64_t)t.b * a.H + t.h) * a.S;
-    TileStream<4> ks = make_tile_stream<4>(k, a.ss, 0, wave, lane);
-    TileStream<4> vs = make_tile_stream<4>(v, a.ss, 0, wave, lane);
+    TileStream<kFwdWaves> ks = make_tile_stream<kFwdWaves>(k, a.ss, 0, wave, lane);
+    TileStream<kFwdWaves> vs = make_tile_stream<kFwdWaves>(v, a.ss, 0, wave, lane);
 
     const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
     const int ntiles = (int)(last_row / kBk) + 1;
@@ -445,54 +555,66 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a)
     const int wave_first_diag = (int)(i0w / kBk);
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    for (int jt = 0; jt < ntiles; ++jt) {
-        LDS_AS unsigned char *Ks = lds + (jt & 1) * 2 * kTileBytes, *Vs = Ks + kTileBytes;
+    const LdsAddr ad = make_lds_addr(lds, la);
+    const uint32_t (&row_addr)[8] = ad.row;
+    const uint32_t (&tr_addr)[4][2] = ad.tr;
+
+    auto tile_step = [&](auto bufc, int jt) {
+        constexpr int BUF = decltype(bufc)::value;
+        constexpr int kOff = BUF * 2 * kTileBytes, vOff = kOff + kTileBytes;
+        constexpr int nOff = (BUF ^ 1) * 2 * kTileBytes;
         wait_fills();
         __syncthreads();
         if (jt + 1 < ntiles) {
-            LDS_AS unsigned char *Kn = lds + ((jt + 1) & 1) * 2 * kTileBytes;
-            fill_tile_async(Kn, ks, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
-            fill_tile_async(Kn + kTileBytes, vs, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
+            fill_tile_async(lds + nOff, ks, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
+            fill_tile_async(lds + nOff + kTileBytes, vs, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
         }
-        if (jt >= wave_first_tile_masked) continue;
+        if (jt >= wave_first_tile_masked) return;
         const bool diag = jt >= wave_first_diag;
         const int thr = (int)(i - (int64_t)jt * kBk) - 4 * half;
-#pragma unroll 1
-        for (int jb = 0; jb < 2; ++jb) {
+        static_for<0, 2>([&](auto jbc) {
+            constexpr int jb = decltype(jbc)::value;
+            // S^T and dP^T blocks: item n = (kc = n/2, K or V = n%2), row operands read 4 MFMAs ahead
             f32x16 s, dp;
             {
-                bf16x8 ka[8];
-#pragma unroll
-                for (int kc = 0; kc < 8; ++kc) ka[kc] = lds_row_operand(Ks, la.row_op[kc] + jb * 8192);
-                s = mfma32(ka[0], qB[0], zero);
-#pragma unroll
-                for (int kc = 1; kc < 8; ++kc) s = mfma32(ka[kc], qB[kc], s);
+                bf16x8 ring[5];
+                auto issue = [&](auto n, bf16x8 &slot) {
+                    constexpr int kc = decltype(n)::value / 2, isv = decltype(n)::value % 2;
+                    lds_issue_b128<jb * 8192 + (isv ? vOff : kOff)>(slot, row_addr[kc]);
+                };
+                lds_pipeline_prologue<16, 4, 1>(ring, issue);
+                lds_pipeline_body<16, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
+                    constexpr int kc = decltype(n)::value / 2, isv = decltype(n)::value % 2;
+                    if constexpr (isv) dp = mfma32(slot, gB[kc], kc == 0 ? zero : dp);
+                    else s = mfma32(slot, qB[kc], kc == 0 ? zero : s);
+                });
             }
-            {
-                bf16x8 va[8];
-#pragma unroll
-                for (int kc = 0; kc < 8; ++kc) va[kc] = lds_row_operand(Vs, la.row_op[kc] + jb * 8192);
-                dp = mfma32(va[0], gB[0], zero);
-#pragma unroll
-                for (int kc = 1; kc < 8; ++kc) dp = mfma32(va[kc], gB[kc], dp);
-            }
+            // dQ^T += K^T dS^T : A = K^T (transposed read of the same K tile), B = dS^T registers.
+            // item n = (sub = n/4, cb = n%4); the first operands are requested before the VALU work
+            TrSlot kring[4];
+            auto k_issue = [&](auto n, TrSlot &slot) {
+                constexpr int sub = decltype(n)::value / 4, cb = decltype(n)::value % 4;
+                lds_issue_tr<(2 * jb + sub) * 4096 + kOff>(slot, tr_addr[cb][0], tr_addr[cb][1]);
+            };
+            lds_pipeline_prologue<8, 3, 2>(kring, k_issue);
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -lse2));
                 if (diag && (32 * jb + 8 * (e >> 2) + (e & 3) > thr)) p = 0.f;
                 s[e] = p * (dp[e] - Di);           // dS
             }
-            // dQ^T += K^T dS^T : A = K^T (transposed read of the same K tile), B = dS^T registers
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                bf16x8 kt[4];
-#pragma unroll
-                for (int cb = 0; cb < 4; ++cb) kt[cb] = lds_tr_operand(Ks, la, cb, 2 * jb + sub);
-                const bf16x8 dsB = pack8(s, 8 * sub);
-#pragma unroll
-                for (int cb = 0; cb < 4; ++cb) accQ[cb] = mfma32(kt[cb], dsB, accQ[cb]);
-            }
-        }
+            bf16x8 dsB[2];
+            dsB[0] = pack8(s, 0);
+            dsB[1] = pack8(s, 8);
+            lds_pipeline_body<8, 3, 2>(kring, k_issue, [&](auto n, TrSlot &slot) {
+                constexpr int sub = decltype(n)::value / 4, cb = decltype(n)::value % 4;
+                accQ[cb] = mfma32(tr_operand(slot), dsB[sub], accQ[cb]);
+            });
+        });
+    };
+    for (int jt = 0; jt < ntiles; jt += 2) {
+        tile_step(IntC<0>{}, jt);
+        if (jt + 1 < ntiles) tile_step(IntC<1>{}, jt + 1);
     }
     if (i < a.S) {
         __bf16 *dq = static_cast<__bf16 *>(a.dq) + base + i * a.ss;
@@ -520,7 +642,8 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
     LDS_AS unsigned char *Px = lds + 4 * kTileBytes;
     LDS_AS float *Stat = (LDS_AS float *)(Px + 32768);      // [buf][2][64]
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
     const int pair = wave & 3;
     const bool v_role = wave < 4;
     const LaneAddr la = make_lane_addr(lane);
@@ -568,16 +691,24 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
     if (tid < 128) Stat[tid] = sreg;
     LDS_AS unsigned char *Pw = Px + pair * 8192 + lane * 16;   // + ib*4096 + 1024*(e/4)
 
-    for (int it = it0; it < nit; ++it) {
-        const int cur = (it - it0) & 1;
-        LDS_AS unsigned char *Qs = lds + cur * 2 * kTileBytes, *Gs = Qs + kTileBytes;
-        const LDS_AS float *Ls = Stat + cur * 128, *Ds = Ls + 64;
+    const LdsAddr ad = make_lds_addr(lds, la);
+    const uint32_t (&row_addr)[8] = ad.row;
+    const uint32_t (&tr_addr)[4][2] = ad.tr;
+
+    // The two roles run separate copies of the loop (the role is a compile-time constant inside),
+    // with identical barrier sequences.
+    auto role_loop = [&](auto rolec) {
+    constexpr bool VR = decltype(rolec)::value;
+    auto tile_step = [&](auto bufc, int it) {
+        constexpr int BUF = decltype(bufc)::value;
+        constexpr int qOff = BUF * 2 * kTileBytes, gOff = qOff + kTileBytes;
+        constexpr int nOff = (BUF ^ 1) * 2 * kTileBytes;
+        const LDS_AS float *Ls = Stat + BUF * 128, *Ds = Ls + 64;
         wait_fills();
         __syncthreads();          // tile `it` and its statistics are complete; the other buffers are free
         if (it + 1 < nit) {
-            LDS_AS unsigned char *Qn = lds + (cur ^ 1) * 2 * kTileBytes;
-            fill_tile_async(Qn, qs, q, a.ss, (int64_t)(it + 1) * kBq, a.S, wave, lane);
-            fill_tile_async(Qn + kTileBytes, gs, g, a.ss, (int64_t)(it + 1) * kBq, a.S, wave, lane);
+            fill_tile_async(lds + nOff, qs, q, a.ss, (int64_t)(it + 1) * kBq, a.S, wave, lane);
+            fill_tile_async(lds + nOff + kTileBytes, gs, g, a.ss, (int64_t)(it + 1) * kBq, a.S, wave, lane);
             sreg = load_stat(it + 1);
         }
         const int64_t i0 = (int64_t)it * kBq;
@@ -586,18 +717,30 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
         const int thr = (int)(j - i0) - 4 * half;     // query offset e' is visible iff e' >= thr
         bf16x8 pB[4];                                 // V-wave: P chunks [2*ib + sub]
         f32x16 dp[2];                                 // K-wave: dP blocks
+        TrSlot tring[4];                              // transposed operands of the second half
+        // second half: item n = (qi = n/4, cb = n%4), A = dO^T (V-wave) or Q^T (K-wave)
+        auto t_issue = [&](auto n, TrSlot &slot) {
+            constexpr int qi = decltype(n)::value / 4, cb = decltype(n)::value % 4;
+            lds_issue_tr<qi * 4096 + (VR ? gOff : qOff)>(slot, tr_addr[cb][0], tr_addr[cb][1]);
+        };
 
         // ---- first half: scores and probabilities (V-wave), dP (K-wave)
         if (active) {
-            if (v_role) {
-#pragma unroll
-                for (int ib = 0; ib < 2; ++ib) {
-                    bf16x8 qa[8];
-#pragma unroll
-                    for (int kc = 0; kc < 8; ++kc) qa[kc] = lds_row_operand(Qs, la.row_op[kc] + ib * 8192);
-                    f32x16 s = mfma32(qa[0], wB[0], zero);
-#pragma unroll
-                    for (int kc = 1; kc < 8; ++kc) s = mfma32(qa[kc], wB[kc], s);
+            if constexpr (VR) {
+                static_for<0, 2>([&](auto ibc) {
+                    constexpr int ib = decltype(ibc)::value;
+                    f32x16 s;
+                    {
+                        bf16x8 ring[5];
+                        auto issue = [&](auto n, bf16x8 &slot) {
+                            lds_issue_b128<ib * 8192 + qOff>(slot, row_addr[decltype(n)::value]);
+                        };
+                        lds_pipeline_prologue<8, 4, 1>(ring, issue);
+                        lds_pipeline_body<8, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
+                            constexpr int kc = decltype(n)::value;
+                            s = mfma32(slot, wB[kc], kc == 0 ? zero : s);
+                        });
+                    }
                     // s: lane = key j, register e = query row 32*ib + 8*(e/4) + 4*half + e%4
 #pragma unroll
                     for (int gq = 0; gq < 4; ++gq) {
@@ -617,58 +760,63 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
                         const f32x4 p4 = {s[4 * gq], s[4 * gq + 1], s[4 * gq + 2], s[4 * gq + 3]};
                         *reinterpret_cast<LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024) = p4;
                     }
-                }
+                });
             } else {
-#pragma unroll
-                for (int ib = 0; ib < 2; ++ib) {
-                    bf16x8 ga[8];
-#pragma unroll
-                    for (int kc = 0; kc < 8; ++kc) ga[kc] = lds_row_operand(Gs, la.row_op[kc] + ib * 8192);
-                    dp[ib] = mfma32(ga[0], wB[0], zero);
-#pragma unroll
-                    for (int kc = 1; kc < 8; ++kc) dp[ib] = mfma32(ga[kc], wB[kc], dp[ib]);
-                }
+                static_for<0, 2>([&](auto ibc) {
+                    constexpr int ib = decltype(ibc)::value;
+                    bf16x8 ring[5];
+                    auto issue = [&](auto n, bf16x8 &slot) {
+                        lds_issue_b128<ib * 8192 + gOff>(slot, row_addr[decltype(n)::value]);
+                    };
+                    lds_pipeline_prologue<8, 4, 1>(ring, issue);
+                    lds_pipeline_body<8, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
+                        constexpr int kc = decltype(n)::value;
+                        dp[ib] = mfma32(slot, wB[kc], kc == 0 ? zero : dp[ib]);
+                    });
+                });
             }
+            // the transposed operands do not depend on P: request the first ones before the barrier
+            lds_pipeline_prologue<16, 3, 2>(tring, t_issue);
         }
         __syncthreads();          // P of this tile is in LDS
         // ---- second half: dV (V-wave), dS and dK (K-wave)
         if (active) {
-            if (v_role) {
-#pragma unroll
-                for (int qi = 0; qi < 4; ++qi) {
-                    bf16x8 gt[4];
-#pragma unroll
-                    for (int cb = 0; cb < 4; ++cb) gt[cb] = lds_tr_operand(Gs, la, cb, qi);
-#pragma unroll
-                    for (int cb = 0; cb < 4; ++cb) acc[cb] = mfma32(gt[cb], pB[qi], acc[cb]);
-                }
+            if constexpr (VR) {
+                lds_pipeline_body<16, 3, 2>(tring, t_issue, [&](auto n, TrSlot &slot) {
+                    constexpr int qi = decltype(n)::value / 4, cb = decltype(n)::value % 4;
+                    acc[cb] = mfma32(tr_operand(slot), pB[qi], acc[cb]);
+                });
             } else {
+                bf16x8 dsB[4];
 #pragma unroll
                 for (int ib = 0; ib < 2; ++ib) {
+                    f32x16 ds;
 #pragma unroll
-                    for (int sub = 0; sub < 2; ++sub) {
-                        f32x16 ds;
+                    for (int gq = 0; gq < 4; ++gq) {
+                        // registers 4*gq + r of the block = query rows 32*ib + 8*gq + 4*half + r
+                        const f32x4 p4 = *reinterpret_cast<const LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024);
+                        const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * ib + 8 * gq + 4 * half);
 #pragma unroll
-                        for (int gg = 0; gg < 2; ++gg) {
-                            // registers 8*sub + 4*gg + r of the block = query rows 16*sub + 8*gg + 4*half + r
-                            const int gq = 2 * sub + gg;
-                            const f32x4 p4 = *reinterpret_cast<const LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024);
-                            const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * ib + 8 * gq + 4 * half);
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) ds[4 * gg + r] = p4[r] * (dp[ib][4 * gq + r] - d4[r]);
-                        }
-                        bf16x8 qt[4];
-#pragma unroll
-                        for (int cb = 0; cb < 4; ++cb) qt[cb] = lds_tr_operand(Qs, la, cb, 2 * ib + sub);
-                        const bf16x8 dsB = pack8(ds, 0);
-#pragma unroll
-                        for (int cb = 0; cb < 4; ++cb) acc[cb] = mfma32(qt[cb], dsB, acc[cb]);
+                        for (int r = 0; r < 4; ++r) ds[4 * gq + r] = p4[r] * (dp[ib][4 * gq + r] - d4[r]);
                     }
+                    dsB[2 * ib] = pack8(ds, 0);
+                    dsB[2 * ib + 1] = pack8(ds, 8);
                 }
+                lds_pipeline_body<16, 3, 2>(tring, t_issue, [&](auto n, TrSlot &slot) {
+                    constexpr int qi = decltype(n)::value / 4, cb = decltype(n)::value % 4;
+                    acc[cb] = mfma32(tr_operand(slot), dsB[qi], acc[cb]);
+                });
             }
         }
-        if (it + 1 < nit && tid < 128) Stat[(cur ^ 1) * 128 + tid] = sreg;
+        if (it + 1 < nit && tid < 128) Stat[(BUF ^ 1) * 128 + tid] = sreg;
+    };
+    for (int it = it0; it < nit; it += 2) {
+        tile_step(IntC<0>{}, it);
+        if (it + 1 < nit) tile_step(IntC<1>{}, it + 1);
     }
+    };
+    if (v_role) role_loop(IntC<1>{});
+    else role_loop(IntC<0>{});
     if (j < a.S) {
         __bf16 *out = static_cast<__bf16 *>(v_role ? a.dv : a.dk) + base + j * a.ss;
         store_acc_T(out, acc, v_role ? 1.f : a.scale, half);
@@ -682,7 +830,7 @@ hipError_t launch_attn_fwd_bf16(const AttnArgs &a, hipStream_t st)
     const int64_t nqt = (a.S + kFwdBq - 1) / kFwdBq;
     const int64_t blocks = nqt * a.H * a.B;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    attn_fwd_bf16_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>(a);
+    attn_fwd_bf16_kernel<<<dim3((unsigned)blocks), 64 * kFwdWaves, 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -697,7 +845,7 @@ hipError_t launch_attn_bwd_bf16(const AttnArgs &a, hipStream_t st)
     if ((e = record_stage(a, 1, st)) != hipSuccess) return e;
     attn_bwd_dkdv_bf16_kernel<<<dim3((unsigned)(nkt * a.H * a.B)), 512, 0, st>>>(a);
     if ((e = record_stage(a, 2, st)) != hipSuccess) return e;
-    attn_bwd_dq_bf16_kernel<<<dim3((unsigned)(nqt * a.H * a.B)), 256, 0, st>>>(a);
+    attn_bwd_dq_bf16_kernel<<<dim3((unsigned)(nqt * a.H * a.B)), 64 * kFwdWaves, 0, st>>>(a);
     if ((e = record_stage(a, 3, st)) != hipSuccess) return e;
     return hipGetLastError();
 }
