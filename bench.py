@@ -24,6 +24,17 @@ if ROOT not in sys.path:
 METRIC = "attn fwd+bwd TFLOP/s (% bf16 MFMA peak) at S=256K/1M; swap-overlap fraction"
 BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 
+# HBM bytes per launch (read + write) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes
+# over this same command, scaled by what the counters read for a copy kernel of known size
+# (profiles/attn_c5_counters.md).  Counters cannot be read from inside the benchmark, so the
+# figures are carried here per workload; a workload that was not profiled reports null.
+GIB = float(1 << 30)
+MEASURED_HBM_TRAFFIC_BYTES = {
+    "C5": {"attn_fwd_bf16_kernel": (418.7 + 1.02) * GIB,
+           "attn_bwd_dkdv_bf16_kernel": (270.3 + 2.00) * GIB,
+           "attn_bwd_dq_bf16_kernel": (731.8 + 1.00) * GIB},
+}
+
 
 def cpu_baseline(cfg, q, k, v, g, scale, budget_s=15.0):
     """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
@@ -151,7 +162,11 @@ def main():
     dom_ms, dom_flop = kernels[dom]
     achieved = dom_flop / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
+                "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(args.config, {}).get(dom),
+                "traffic_unit": "bytes of HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled)",
+                "algorithmic_hbm_bytes": (4.0 if dom != "attn_bwd_dq_bf16_kernel" else 5.0) * B * S * H * d * 2
+                                         + (2.0 if dom == "attn_bwd_dkdv_bf16_kernel" else 1.0) * B * S * H * d * 2,
                 "avg_launch_ms": dom_ms,
                 "all_kernels": {n: {"avg_ms": ms, "TFLOP/s": fl / (ms * 1e-3) / 1e12,
                                     "frac": fl / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
