@@ -165,8 +165,10 @@ def main():
                 "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                 "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(args.config, {}).get(dom),
                 "traffic_unit": "bytes of HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled)",
-                "algorithmic_hbm_bytes": (4.0 if dom != "attn_bwd_dq_bf16_kernel" else 5.0) * B * S * H * d * 2
-                                         + (2.0 if dom == "attn_bwd_dkdv_bf16_kernel" else 1.0) * B * S * H * d * 2,
+                # tensors each kernel must read or write once: fwd Q,K,V,O; dK/dV Q,K,V,dO,dK,dV;
+                # dQ Q,K,V,dO,dQ (the [B,H,S] statistics are 1/64 of a tensor and left out)
+                "algorithmic_hbm_bytes": {"attn_fwd_bf16_kernel": 4, "attn_bwd_dkdv_bf16_kernel": 6,
+                                          "attn_bwd_dq_bf16_kernel": 5}[dom] * B * S * H * d * 2,
                 "avg_launch_ms": dom_ms,
                 "all_kernels": {n: {"avg_ms": ms, "TFLOP/s": fl / (ms * 1e-3) / 1e12,
                                     "frac": fl / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}

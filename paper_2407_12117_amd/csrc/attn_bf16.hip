@@ -20,6 +20,7 @@
 //   16*q + 8*(e/4) + 4*half + e%4.
 // The matching A operand is a TRANSPOSED read of a row-major LDS tile, done by the LDS
 // transpose load ds_read_b64_tr_b16 (two per operand: rows 4*half+0..3 and 8+4*half+0..3).
+// All operand reads are issued by hand several MFMAs ahead (see lds_pipeline_* below).
 //
 // LDS tiles are 64 rows x 128 bf16, row-major, 256 bytes per row, no padding; the sixteen
 // 16-byte chunks of row r are stored at chunk position  c ^ swz(r),
@@ -99,24 +100,6 @@ __device__ __forceinline__ LdsAddr make_lds_addr(const LDS_AS unsigned char *bas
     return ad;
 }
 
-__device__ __forceinline__ bf16x8 lds_row_operand(const LDS_AS unsigned char *tile, int off)
-{
-    return *reinterpret_cast<const LDS_AS bf16x8 *>(tile + off);
-}
-
-// 8 contraction slots of chunk q (16 tile rows) for tile column 32*cb + l32
-__device__ __forceinline__ bf16x8 lds_tr_operand(const LDS_AS unsigned char *tile, const LaneAddr &la,
-                                                 int cb, int q)
-{
-    // rows 16q .. 16q+15 keep swz() of rows 0..15, so q only adds 16*256 bytes
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (LDS_AS s16x4 *)(tile + la.tr_op[cb][0] + q * 4096));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (LDS_AS s16x4 *)(tile + la.tr_op[cb][1] + q * 4096));
-    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, both);
-}
-
 // 8 fp32 -> 8 bf16 (round to nearest even)
 __device__ __forceinline__ bf16x8 pack8(const f32x16 &x, int first)
 {
@@ -129,30 +112,6 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &x, int first)
         out[e + 1] = r[1];
     }
     return out;
-}
-
-// ---- staging of a 64-row x 128-col bf16 tile by 256 threads ---------------------------
-// 16-byte global loads (16 lanes cover one 256-byte row), rows beyond S read as zero.
-struct RowRegs { u32x4 r[4]; };
-
-__device__ __forceinline__ void load_rows(RowRegs &t, const __bf16 *src, int64_t ss, int64_t r0,
-                                          int64_t S, int tid)
-{
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        const int r = 16 * n + (tid >> 4), c16 = tid & 15;
-        t.r[n] = u32x4{0u, 0u, 0u, 0u};
-        if (r0 + r < S) t.r[n] = *reinterpret_cast<const u32x4 *>(src + (r0 + r) * ss + c16 * 8);
-    }
-}
-
-__device__ __forceinline__ void store_rows(LDS_AS unsigned char *tile, const RowRegs &t, int tid)
-{
-    // row 16n + tid/16 has the same swz() for every n
-    const int r = tid >> 4, c16 = tid & 15;
-    const int off = r * 256 + ((c16 ^ swz(r)) << 4);
-#pragma unroll
-    for (int n = 0; n < 4; ++n) *reinterpret_cast<LDS_AS u32x4 *>(tile + off + n * 4096) = t.r[n];
 }
 
 // Writes a 32(col i) x 128(row c) fp32 accumulator set held as acc[cb][v] (D layout with
