@@ -683,43 +683,76 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
             lds_issue_tr<qi * 4096 + (VR ? gOff : qOff)>(slot, tr_addr[cb][0], tr_addr[cb][1]);
         };
 
-        // ---- first half: scores and probabilities (V-wave), dP (K-wave)
+        // V-wave: scores and probabilities of one 32-query block; P goes to the K-wave through LDS
+        auto v_scores = [&](auto ibc) {
+            constexpr int ib = decltype(ibc)::value;
+            f32x16 s;
+            {
+                bf16x8 ring[5];
+                auto issue = [&](auto n, bf16x8 &slot) {
+                    lds_issue_b128<ib * 8192 + qOff>(slot, row_addr[decltype(n)::value]);
+                };
+                lds_pipeline_prologue<8, 4, 1>(ring, issue);
+                lds_pipeline_body<8, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
+                    constexpr int kc = decltype(n)::value;
+                    s = mfma32(slot, wB[kc], kc == 0 ? zero : s);
+                });
+            }
+            // s: lane = key j, register e = query row 32*ib + 8*(e/4) + 4*half + e%4
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * ib + 8 * gq + 4 * half);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int e = 4 * gq + r;
+                    float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[r]));
+                    if (diag && (32 * ib + 8 * gq + r < thr)) p = 0.f;
+                    s[e] = p;
+                }
+            }
+            pB[2 * ib] = pack8(s, 0);
+            pB[2 * ib + 1] = pack8(s, 8);
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 p4 = {s[4 * gq], s[4 * gq + 1], s[4 * gq + 2], s[4 * gq + 3]};
+                *reinterpret_cast<LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024) = p4;
+            }
+        };
+        // K-wave: dS of one 32-query block from the V-wave's P, then dK^T += Q^T dS over that block
+        auto k_block = [&](auto ibc) {
+            constexpr int ib = decltype(ibc)::value;
+            TrSlot ring[4];
+            auto issue = [&](auto n, TrSlot &slot) {
+                constexpr int qi = 2 * ib + decltype(n)::value / 4, cb = decltype(n)::value % 4;
+                lds_issue_tr<qi * 4096 + qOff>(slot, tr_addr[cb][0], tr_addr[cb][1]);
+            };
+            lds_pipeline_prologue<8, 3, 2>(ring, issue);
+            f32x16 ds;
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                // registers 4*gq + r of the block = query rows 32*ib + 8*gq + 4*half + r
+                const f32x4 p4 = *reinterpret_cast<const LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024);
+                const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * ib + 8 * gq + 4 * half);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ds[4 * gq + r] = p4[r] * (dp[ib][4 * gq + r] - d4[r]);
+            }
+            bf16x8 dsB[2];
+            dsB[0] = pack8(ds, 0);
+            dsB[1] = pack8(ds, 8);
+            lds_pipeline_body<8, 3, 2>(ring, issue, [&](auto n, TrSlot &slot) {
+                constexpr int sub = decltype(n)::value / 4, cb = decltype(n)::value % 4;
+                acc[cb] = mfma32(tr_operand(slot), dsB[sub], acc[cb]);
+            });
+        };
+
+        // Three intervals per tile, so that in each of them both waves of a pair have MFMA work
+        // and the exponentials / dS arithmetic of one overlap the MFMAs of the other:
+        //   1: V scores+P(block 0)      | K dP(blocks 0,1)
+        //   2: V scores+P(block 1)      | K dS,dK(block 0)
+        //   3: V dV(blocks 0,1)         | K dS,dK(block 1)
         if (active) {
             if constexpr (VR) {
-                static_for<0, 2>([&](auto ibc) {
-                    constexpr int ib = decltype(ibc)::value;
-                    f32x16 s;
-                    {
-                        bf16x8 ring[5];
-                        auto issue = [&](auto n, bf16x8 &slot) {
-                            lds_issue_b128<ib * 8192 + qOff>(slot, row_addr[decltype(n)::value]);
-                        };
-                        lds_pipeline_prologue<8, 4, 1>(ring, issue);
-                        lds_pipeline_body<8, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
-                            constexpr int kc = decltype(n)::value;
-                            s = mfma32(slot, wB[kc], kc == 0 ? zero : s);
-                        });
-                    }
-                    // s: lane = key j, register e = query row 32*ib + 8*(e/4) + 4*half + e%4
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * ib + 8 * gq + 4 * half);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int e = 4 * gq + r;
-                            float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[r]));
-                            if (diag && (32 * ib + 8 * gq + r < thr)) p = 0.f;
-                            s[e] = p;
-                        }
-                    }
-                    pB[2 * ib] = pack8(s, 0);
-                    pB[2 * ib + 1] = pack8(s, 8);
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        const f32x4 p4 = {s[4 * gq], s[4 * gq + 1], s[4 * gq + 2], s[4 * gq + 3]};
-                        *reinterpret_cast<LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024) = p4;
-                    }
-                });
+                v_scores(IntC<0>{});
             } else {
                 static_for<0, 2>([&](auto ibc) {
                     constexpr int ib = decltype(ibc)::value;
@@ -734,37 +767,22 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
                     });
                 });
             }
-            // the transposed operands do not depend on P: request the first ones before the barrier
-            lds_pipeline_prologue<16, 3, 2>(tring, t_issue);
         }
-        __syncthreads();          // P of this tile is in LDS
-        // ---- second half: dV (V-wave), dS and dK (K-wave)
+        __syncthreads();          // P of block 0 is in LDS
+        if (active) {
+            if constexpr (VR) v_scores(IntC<1>{});
+            else k_block(IntC<0>{});
+        }
+        __syncthreads();          // P of block 1 is in LDS
         if (active) {
             if constexpr (VR) {
+                lds_pipeline_prologue<16, 3, 2>(tring, t_issue);
                 lds_pipeline_body<16, 3, 2>(tring, t_issue, [&](auto n, TrSlot &slot) {
                     constexpr int qi = decltype(n)::value / 4, cb = decltype(n)::value % 4;
                     acc[cb] = mfma32(tr_operand(slot), pB[qi], acc[cb]);
                 });
             } else {
-                bf16x8 dsB[4];
-#pragma unroll
-                for (int ib = 0; ib < 2; ++ib) {
-                    f32x16 ds;
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        // registers 4*gq + r of the block = query rows 32*ib + 8*gq + 4*half + r
-                        const f32x4 p4 = *reinterpret_cast<const LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024);
-                        const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * ib + 8 * gq + 4 * half);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) ds[4 * gq + r] = p4[r] * (dp[ib][4 * gq + r] - d4[r]);
-                    }
-                    dsB[2 * ib] = pack8(ds, 0);
-                    dsB[2 * ib + 1] = pack8(ds, 8);
-                }
-                lds_pipeline_body<16, 3, 2>(tring, t_issue, [&](auto n, TrSlot &slot) {
-                    constexpr int qi = decltype(n)::value / 4, cb = decltype(n)::value % 4;
-                    acc[cb] = mfma32(tr_operand(slot), dsB[qi], acc[cb]);
-                });
+                k_block(IntC<1>{});
             }
         }
         if (it + 1 < nit && tid < 128) Stat[(BUF ^ 1) * 128 + tid] = sreg;
