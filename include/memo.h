@@ -156,6 +156,74 @@ memo_status memo_swap_in(void *dev_act, int64_t S, int64_t row_bytes, double alp
 memo_status memo_solve_alpha(double s_in, double s_attn, double s_oth, double bandwidth,
                              double t_layer, int32_t n_layers, double m_cpu, double *alpha_out);
 
+/*
+ * Two rounding buffers over n layers (Section 4.1, Figure 5; Section 4.3.4, the
+ * three-stream schedule).
+ *
+ * A layer's saved tensors live together in one of two device buffers (layer i uses
+ * buffer i % 2).  Each tensor t is [S, row_bytes[t]] bytes with its own fraction
+ * alpha[t] (1 for the layer input and the attention output, the solved alpha for the
+ * rest).  memo_buffer_plan_make lays them out: every tensor whole in the device buffer
+ * at dev_offset, the swapped prefixes back to back in a per-layer host slot at
+ * host_offset, both rounded up to 256 bytes (the paper does not specify a packing).
+ */
+typedef struct {
+    int64_t row_bytes;          /* > 0 */
+    double alpha;               /* finite, in [0,1] */
+} memo_tensor_desc;
+
+typedef struct {
+    int64_t dev_offset;         /* byte offset of the tensor in a rounding buffer */
+    int64_t host_offset;        /* byte offset of its swapped prefix in a layer's host slot */
+    int64_t k_swapped;          /* rows [0,k) swapped, rows [k,S) to regenerate */
+    size_t bytes_swapped;       /* k_swapped * row_bytes */
+} memo_tensor_slot;
+
+/*
+ * Host-side arithmetic only.  slots_out has room for n_tensors entries; dev_bytes_out /
+ * host_bytes_out receive the size of one rounding buffer / of one layer's host slot.
+ * MEMO_ERR_INVALID_ARG on null pointers, n_tensors < 1, S < 1 or a bad descriptor.
+ */
+memo_status memo_buffer_plan_make(int64_t S, int32_t n_tensors, const memo_tensor_desc *tensors,
+                                  memo_tensor_slot *slots_out, size_t *dev_bytes_out,
+                                  size_t *host_bytes_out);
+
+/*
+ * The schedule itself.  A memo_sched owns 4*n_layers HIP events and nothing else; the
+ * caller owns the two device buffers (dev_bytes each), the pinned host store and the
+ * three streams (compute, offload, prefetch; all three must differ for the copies to
+ * overlap, but any may coincide).  The host store must hold (n_layers - 2) layer
+ * slots: MEMO_ERR_HOST_CAPACITY otherwise (the second constraint of the alpha problem).
+ *
+ * Per iteration the caller brackets each layer's work on the compute stream:
+ *   for i = 0 .. n-1:   memo_sched_forward_begin(i);  <forward of layer i writes buffer i%2>
+ *                       memo_sched_forward_end(i);
+ *   for i = n-1 .. 0:   memo_sched_backward_begin(i); <regenerate rows [k,S); backward>
+ *                       memo_sched_backward_end(i);
+ * forward_begin(i)  makes the compute stream wait until layer i-2's offload has left
+ *                   buffer i%2;
+ * forward_end(i)    queues the offload of layer i's prefixes on the offload stream behind
+ *                   the forward (not for the last two layers, which turn round at once);
+ * backward_begin(i) makes the compute stream wait for the prefetch of layer i;
+ * backward_end(i)   queues the prefetch of layer i-2 into buffer i%2 on the prefetch
+ *                   stream behind this backward, so it runs under backward(i-1).
+ * Calls out of this order give MEMO_ERR_INVALID_ARG and queue nothing.  Nothing blocks
+ * the host.  memo_sched_buffer(i) is the device buffer of layer i.
+ */
+typedef struct memo_sched memo_sched;
+
+memo_status memo_sched_create(memo_sched **out, int32_t n_layers, int64_t S, int32_t n_tensors,
+                              const memo_tensor_desc *tensors, void *dev_buffer0,
+                              void *dev_buffer1, void *host_store, size_t host_capacity_bytes,
+                              void *compute_stream, void *offload_stream, void *prefetch_stream);
+memo_status memo_sched_forward_begin(memo_sched *s, int32_t layer);
+memo_status memo_sched_forward_end(memo_sched *s, int32_t layer);
+memo_status memo_sched_backward_begin(memo_sched *s, int32_t layer);
+memo_status memo_sched_backward_end(memo_sched *s, int32_t layer);
+void *memo_sched_buffer(const memo_sched *s, int32_t layer);
+/* Waits for nothing: the caller synchronises its streams first.  NULL is accepted. */
+memo_status memo_sched_destroy(memo_sched *s);
+
 /* Pinned host memory helpers (hipHostMalloc / hipHostFree). */
 memo_status memo_host_alloc(void **host_ptr, size_t bytes);
 memo_status memo_host_free(void *host_ptr);

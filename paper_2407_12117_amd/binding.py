@@ -26,6 +26,9 @@ EXPORTS = [
     "memo_split_tokens",
     "memo_swap_plan_make", "memo_swap_out", "memo_swap_in", "memo_solve_alpha",
     "memo_host_alloc", "memo_host_free", "memo_status_str",
+    "memo_buffer_plan_make", "memo_sched_create", "memo_sched_forward_begin",
+    "memo_sched_forward_end", "memo_sched_backward_begin", "memo_sched_backward_end",
+    "memo_sched_buffer", "memo_sched_destroy",
 ]
 
 
@@ -42,6 +45,15 @@ class MemoSwapPlan(ctypes.Structure):
                 ("k_swapped", ctypes.c_int64), ("n_recompute", ctypes.c_int64),
                 ("bytes_swapped", ctypes.c_int64), ("bytes_dropped", ctypes.c_int64),
                 ("recompute_byte_offset", ctypes.c_int64)]
+
+
+class MemoTensorDesc(ctypes.Structure):
+    _fields_ = [("row_bytes", ctypes.c_int64), ("alpha", ctypes.c_double)]
+
+
+class MemoTensorSlot(ctypes.Structure):
+    _fields_ = [("dev_offset", ctypes.c_int64), ("host_offset", ctypes.c_int64),
+                ("k_swapped", ctypes.c_int64), ("bytes_swapped", ctypes.c_size_t)]
 
 
 class MemoError(RuntimeError):
@@ -90,6 +102,21 @@ def lib():
     L.memo_host_free.restype = ctypes.c_int
     L.memo_status_str.argtypes = [ctypes.c_int]
     L.memo_status_str.restype = ctypes.c_char_p
+    tdp = ctypes.POINTER(MemoTensorDesc)
+    L.memo_buffer_plan_make.argtypes = [i64, ctypes.c_int32, tdp, ctypes.POINTER(MemoTensorSlot),
+                                        ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    L.memo_buffer_plan_make.restype = ctypes.c_int
+    L.memo_sched_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int32, i64, ctypes.c_int32, tdp,
+                                    vp, vp, vp, sz, vp, vp, vp]
+    L.memo_sched_create.restype = ctypes.c_int
+    for name in ("memo_sched_forward_begin", "memo_sched_forward_end",
+                 "memo_sched_backward_begin", "memo_sched_backward_end"):
+        getattr(L, name).argtypes = [vp, ctypes.c_int32]
+        getattr(L, name).restype = ctypes.c_int
+    L.memo_sched_buffer.argtypes = [vp, ctypes.c_int32]
+    L.memo_sched_buffer.restype = vp
+    L.memo_sched_destroy.argtypes = [vp]
+    L.memo_sched_destroy.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -252,3 +279,81 @@ def memo_solve_alpha(s_in, s_attn, s_oth, bandwidth, t_layer, n_layers, m_cpu):
                                   float(t_layer), int(n_layers), float(m_cpu), ctypes.byref(out)),
            "memo_solve_alpha")
     return out.value
+
+
+def _tensor_descs(tensors):
+    arr = (MemoTensorDesc * len(tensors))()
+    for i, (row_bytes, alpha) in enumerate(tensors):
+        arr[i].row_bytes, arr[i].alpha = int(row_bytes), float(alpha)
+    return arr
+
+
+def memo_buffer_plan_make(S, tensors):
+    """tensors: list of (row_bytes, alpha).  Returns (slots, dev_bytes, host_bytes)."""
+    n = len(tensors)
+    slots = (MemoTensorSlot * max(n, 1))()
+    dev, host = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().memo_buffer_plan_make(int(S), n, _tensor_descs(tensors) if n else None, slots,
+                                       ctypes.byref(dev), ctypes.byref(host)),
+           "memo_buffer_plan_make")
+    out = [{name: int(getattr(slots[i], name)) for name, _ in MemoTensorSlot._fields_}
+           for i in range(n)]
+    return out, int(dev.value), int(host.value)
+
+
+class MemoSched:
+    """Handle of memo_sched_*: two rounding buffers over n layers.  Keeps the caller's
+    buffers, host store and streams alive for as long as the handle lives."""
+
+    def __init__(self, n_layers, S, tensors, dev_buffers, host_store, compute_stream,
+                 offload_stream, prefetch_stream):
+        b0, b1 = dev_buffers
+        for b in (b0, b1):
+            if b.dtype != torch.uint8 or not b.is_contiguous() or not b.is_cuda:
+                raise ValueError("rounding buffers must be contiguous uint8 device tensors")
+        _, dev_bytes, _ = memo_buffer_plan_make(S, tensors)
+        if b0.numel() < dev_bytes or b1.numel() < dev_bytes:
+            raise ValueError(f"rounding buffers must hold {dev_bytes} bytes each")
+        if host_store is not None and not host_store.is_pinned():
+            raise ValueError("host store must be pinned memory")
+        self._keep = (b0, b1, host_store, compute_stream, offload_stream, prefetch_stream)
+        self.n_layers = int(n_layers)
+        handle = ctypes.c_void_p(None)
+        cap = 0 if host_store is None else host_store.numel() * host_store.element_size()
+        _check(lib().memo_sched_create(ctypes.byref(handle), self.n_layers, int(S), len(tensors),
+                                       _tensor_descs(tensors), b0.data_ptr(), b1.data_ptr(),
+                                       None if host_store is None else host_store.data_ptr(), cap,
+                                       _stream_ptr(compute_stream), _stream_ptr(offload_stream),
+                                       _stream_ptr(prefetch_stream)),
+               "memo_sched_create")
+        self._h = handle
+
+    def forward_begin(self, layer):
+        _check(lib().memo_sched_forward_begin(self._h, int(layer)), "memo_sched_forward_begin")
+
+    def forward_end(self, layer):
+        _check(lib().memo_sched_forward_end(self._h, int(layer)), "memo_sched_forward_end")
+
+    def backward_begin(self, layer):
+        _check(lib().memo_sched_backward_begin(self._h, int(layer)), "memo_sched_backward_begin")
+
+    def backward_end(self, layer):
+        _check(lib().memo_sched_backward_end(self._h, int(layer)), "memo_sched_backward_end")
+
+    def buffer(self, layer):
+        """The rounding buffer (uint8 tensor) of a layer."""
+        return self._keep[int(layer) % 2]
+
+    def buffer_ptr(self, layer):
+        return lib().memo_sched_buffer(self._h, int(layer))
+
+    def destroy(self):
+        if self._h is not None and self._h.value:
+            _check(lib().memo_sched_destroy(self._h), "memo_sched_destroy")
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

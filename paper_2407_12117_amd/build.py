@@ -12,6 +12,7 @@ LIB = os.path.join(HERE, "libmemo.so")
 # full NaN semantics because it validates caller input with isnan().
 SOURCES = {
     "memo_api.cpp": [],
+    "memo_sched.cpp": [],
     "attn_f32.hip": [],
     "attn_bf16.hip": ["-fno-honor-nans"],
 }

@@ -146,3 +146,61 @@ def test_alpha_infeasible_cases(oracle):
     assert oracle.alpha_grid(1, 1, 14, 1e9, 1.0, 32, 10.0, 8) == -1.0
     with pytest.raises(mb.MemoError):
         mb.memo_solve_alpha(1, 1, 0, 1, 1.0, 32, 10.0)
+
+
+# ------------------------------------------- rounding buffers (Section 4.1, Figure 5)
+@pytest.mark.parametrize("seed", range(6))
+def test_buffer_plan_matches_oracle(seed):
+    import numpy as np
+    from oracle import memo_sched_oracle as so
+    rng = np.random.default_rng(seed)
+    S = int(rng.integers(1, 5000))
+    tensors = [(int(rng.integers(1, 3000)), float(rng.choice(ALPHAS))) for _ in range(int(rng.integers(1, 20)))]
+    slots, dev, host = mb.memo_buffer_plan_make(S, tensors)
+    oslots, odev, ohost = so.buffer_plan(S, tensors)
+    assert (dev, host) == (odev, ohost)
+    assert slots == oslots
+
+
+def test_buffer_plan_full_size_layer():
+    # one GPU's share of a 7B layer at S = 2^20 (16 tensors of S x 1 KiB)
+    from oracle import memo_sched_oracle as so
+    tensors = [(1024, 1.0), (1024, 1.0)] + [(1024, 0.375)] * 14
+    slots, dev, host = mb.memo_buffer_plan_make(1 << 20, tensors)
+    assert (slots, dev, host) == so.buffer_plan(1 << 20, tensors)
+    assert dev == 16 << 30
+
+
+def test_buffer_plan_and_sched_reject_bad_arguments():
+    L = mb.lib()
+    ok = ctypes.c_void_p(4096)
+    descs = (mb.MemoTensorDesc * 2)()
+    descs[0].row_bytes, descs[0].alpha = 64, 1.0
+    descs[1].row_bytes, descs[1].alpha = 32, 0.5
+    slots = (mb.MemoTensorSlot * 2)()
+    dev, host = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    args = (slots, ctypes.byref(dev), ctypes.byref(host))
+    assert L.memo_buffer_plan_make(16, 2, descs, *args) == mb.MEMO_OK
+    assert L.memo_buffer_plan_make(0, 2, descs, *args) == mb.MEMO_ERR_INVALID_ARG
+    assert L.memo_buffer_plan_make(16, 0, descs, *args) == mb.MEMO_ERR_INVALID_ARG
+    assert L.memo_buffer_plan_make(16, 2, None, *args) == mb.MEMO_ERR_INVALID_ARG
+    descs[1].alpha = 1.25
+    assert L.memo_buffer_plan_make(16, 2, descs, *args) == mb.MEMO_ERR_INVALID_ARG
+    descs[1].alpha = 0.5
+    descs[0].row_bytes = 0
+    assert L.memo_buffer_plan_make(16, 2, descs, *args) == mb.MEMO_ERR_INVALID_ARG
+    descs[0].row_bytes = 64
+
+    h = ctypes.c_void_p(None)
+    create = lambda n, cap, b0=ok, b1=ok, hs=ok: L.memo_sched_create(
+        ctypes.byref(h), n, 16, 2, descs, b0, b1, hs, cap, None, None, None)
+    per_layer = host.value
+    # five layers hold three slots on the host: one byte short is the host out-of-memory case
+    assert create(5, 3 * per_layer - 1) == mb.MEMO_ERR_HOST_CAPACITY and not h.value
+    assert create(0, 1 << 20) == mb.MEMO_ERR_INVALID_ARG
+    assert create(5, 1 << 20, b0=None) == mb.MEMO_ERR_INVALID_ARG
+    assert create(5, 1 << 20, hs=None) == mb.MEMO_ERR_INVALID_ARG
+    assert L.memo_sched_forward_begin(None, 0) == mb.MEMO_ERR_INVALID_ARG
+    assert L.memo_sched_backward_end(None, 0) == mb.MEMO_ERR_INVALID_ARG
+    assert L.memo_sched_buffer(None, 0) is None
+    assert L.memo_sched_destroy(None) == mb.MEMO_OK
