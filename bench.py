@@ -77,6 +77,12 @@ def main():
                     help="skip the separate swap/compute overlap measurement (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy kernel (reference for HBM counters)")
+    ap.add_argument("--schedule", default=None, metavar="S[,S...]",
+                    help="instead of the default step: run the two-rounding-buffer schedule over "
+                         "--layers stand-in layers at these sequence lengths and report the exposed "
+                         "copy time per alpha")
+    ap.add_argument("--layers", type=int, default=6)
+    ap.add_argument("--alphas", default="0,0.25,0.5,0.75,1")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one GPU's share of a tensor-parallel layer); "
@@ -90,6 +96,9 @@ def main():
     mb.lib()                                             # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.schedule:
+        schedule_bench(torch, mb, synth, args)
+        return
     cfg = synth.CONFIGS[args.config]
     assert cfg["dtype"] == "bf16", "bench workloads are the bf16 ones (C2..C5)"
     B, S, H, d = cfg["B"], cfg["S"], cfg["H"], cfg["d"]
@@ -207,6 +216,8 @@ def main():
         swap = None
     else:
         swap = measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, plan, alpha)
+    alpha_solver = solve_alpha_for(mb, S, H, d, fwd_ms * 1e-3,
+                                   swap["d2h_GBps"] * 1e9 if swap and swap["d2h_GBps"] else None)
     out = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -219,10 +230,33 @@ def main():
                    "mfu_convention_TFLOPs": 6.0 * pairs * d * H * B / (ms_per_step * 1e-3) / 1e12},
         "roofline": roofline,
         "swap": swap,
+        "alpha_solver": alpha_solver,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, g, scale)
     print(json.dumps(out), flush=True)
+
+
+def solve_alpha_for(mb, S, H, d, t_fwd_s, bandwidth, n_layers=32, m_cpu=2.0 * 2 ** 40 / 8):
+    """The alpha problem of Section 4.1 fed with what this run measured: T_layer = the attention
+    forward alone (a lower bound of the layer's forward, so alpha is a lower bound too), B = the
+    measured device-to-host rate.  Sizes are one GPU's share of a layer: input and attention
+    output S*H*d 16-bit elements each, the other saved tensors 14 times that (16 in all);
+    n = 32 layers and 2 TiB of host memory shared by 8 GPUs, as in the paper's 7B setting."""
+    if bandwidth is None:
+        return None
+    unit = float(S) * H * d * 2
+    res = {"s_in_bytes": unit, "s_attn_bytes": unit, "s_oth_bytes": 14 * unit,
+           "bandwidth_GBps": bandwidth / 1e9, "t_layer_s": t_fwd_s, "n_layers": n_layers,
+           "m_cpu_bytes": m_cpu}
+    try:
+        res["alpha"] = mb.memo_solve_alpha(unit, unit, 14 * unit, bandwidth, t_fwd_s, n_layers, m_cpu)
+        a_time = (t_fwd_s * bandwidth - 2 * unit) / (14 * unit)
+        a_mem = (m_cpu / (n_layers - 2) - 2 * unit) / (14 * unit)
+        res["binding"] = "none" if res["alpha"] >= 1.0 else ("time" if a_time <= a_mem else "host memory")
+    except mb.MemoError as e:
+        res["alpha"], res["binding"] = None, str(e)
+    return res
 
 
 def measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, plan, alpha):
@@ -245,6 +279,82 @@ def measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, pla
     }
 
     return swap
+
+
+def schedule_bench(torch, mb, synth, args):
+    """Exposed copy time of the rounding-buffer schedule (Section 4.1, Figure 5) against alpha:
+    one training iteration over n stand-in layers (H = 4 heads of d = 128, 16 saved tensors of
+    S x 1 KiB per layer) with swap, minus the same iteration with every layer resident; beside it
+    what three queues that never slow each other would leave exposed given the measured per-layer
+    times and copy rates (each swapped layer pays the excess of its copy over the pass it hides
+    behind, forward and backward), and the alpha the solver picks for them."""
+    from paper_2407_12117_amd import layer_stack as ls
+    H, d, n = 4, 128, args.layers
+    scale = synth.default_scale(d)
+    alphas = [float(a) for a in args.alphas.split(",")]
+    rows = []
+
+    def run(stack, x0, g, iters):
+        stack.forward(x0); stack.backward(g)               # warm-up iteration
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            stack.forward(x0)
+            stack.backward(g)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters
+
+    for S in [int(x) for x in args.schedule.split(",")]:
+        gen = torch.Generator(device="cuda").manual_seed(4242)
+        x0 = torch.randn((S, H * d), generator=gen, device="cuda").to(torch.bfloat16)
+        g = torch.randn((S, H * d), generator=gen, device="cuda").to(torch.bfloat16)
+        iters = max(1, args.steps)
+        res = ls.LayerStack(n, S, H, d, 1.0, scale, swap=False)
+        t_res = run(res, x0, g, iters)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter(); res.forward(x0); torch.cuda.synchronize()
+        t_fwd = (time.perf_counter() - t0) / n
+        t_bwd = t_res / n - t_fwd
+        res.close(); del res
+        torch.cuda.empty_cache()
+        # copy rates on this box, both directions, on one layer's worth of bytes
+        _, _, layer_host = mb.memo_buffer_plan_make(S, ls.layer_tensors(H, d, 1.0))
+        host = torch.empty(max(n - 2, 1) * layer_host, dtype=torch.uint8, pin_memory=True)
+        probe = torch.empty(layer_host, dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+        rate = {}
+        for name, fn in (("d2h", mb.memo_swap_out), ("h2d", mb.memo_swap_in)):
+            fn(probe.view(S, -1), 1.0, host, side); torch.cuda.synchronize()
+            t0 = time.perf_counter(); fn(probe.view(S, -1), 1.0, host, side); torch.cuda.synchronize()
+            rate[name] = layer_host / (time.perf_counter() - t0)
+        del probe
+        unit = float(S) * H * d * 2
+        try:
+            a_star = mb.memo_solve_alpha(unit, unit, 14 * unit, rate["d2h"], t_fwd, n, 1e18)
+        except mb.MemoError:
+            a_star = None
+        for alpha in alphas + ([round(a_star, 3)] if a_star is not None and a_star < 1.0 else []):
+            st = ls.LayerStack(n, S, H, d, alpha, scale, swap=True, host=host)
+            t_swap = run(st, x0, g, iters)
+            hb = st.host_bytes
+            st.close(); del st
+            torch.cuda.empty_cache()
+            pred = {"exposed": max(0, n - 2) * (max(0.0, hb / rate["d2h"] - t_fwd) +
+                                                max(0.0, hb / rate["h2d"] - t_bwd))}
+            rows.append({"S": S, "alpha": alpha, "layer_host_bytes": hb,
+                         "iter_resident_ms": t_res * 1e3, "iter_swapped_ms": t_swap * 1e3,
+                         "exposed_ms": (t_swap - t_res) * 1e3,
+                         "exposed_predicted_ms": pred["exposed"] * 1e3,
+                         "t_fwd_layer_ms": t_fwd * 1e3, "t_bwd_layer_ms": t_bwd * 1e3,
+                         "t_out_ms": hb / rate["d2h"] * 1e3, "t_in_ms": hb / rate["h2d"] * 1e3,
+                         "alpha_solved": a_star})
+            print(f"[schedule] S={S} alpha={alpha} resident {t_res * 1e3:.1f} ms swapped "
+                  f"{t_swap * 1e3:.1f} ms exposed {(t_swap - t_res) * 1e3:.1f} ms "
+                  f"(predicted {pred['exposed'] * 1e3:.1f})", file=sys.stderr, flush=True)
+        del host
+    print(json.dumps({"metric": "exposed copy time of the two-rounding-buffer schedule",
+                      "unit": "ms per iteration", "layers": n, "H": H, "d": d,
+                      "saved_tensors_per_layer": ls.N_SAVED, "rows": rows}), flush=True)
 
 
 if __name__ == "__main__":

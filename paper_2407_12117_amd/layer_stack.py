@@ -57,7 +57,8 @@ class LayerStack:
     buffers (swap=False; the reference the swapped run must reproduce bit for bit)."""
 
     def __init__(self, n_layers, S, H, d, alpha, scale, swap=True, n_saved=N_SAVED,
-                 device="cuda:0"):
+                 device="cuda:0", host=None):
+        """host: optional pinned uint8 tensor to use as the host store (allocated if None)."""
         if d != 128:
             raise ValueError("the bf16 attention path needs d = 128")
         self.n, self.S, self.H, self.d, self.scale, self.swap = n_layers, S, H, d, scale, swap
@@ -75,7 +76,8 @@ class LayerStack:
         self.host = None
         if swap:
             held = max(0, n_layers - 2) * self.host_bytes
-            self.host = torch.empty(max(held, 256), dtype=torch.uint8, pin_memory=True)
+            self.host = host if host is not None else \
+                torch.empty(max(held, 256), dtype=torch.uint8, pin_memory=True)
             self.sched = mb.MemoSched(n_layers, S, self.tensors, self.buffers, self.host,
                                       self.compute, self.offload, self.prefetch)
         shape = (S, H * d)
