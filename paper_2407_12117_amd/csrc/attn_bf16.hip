@@ -206,6 +206,54 @@ __device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, Tile
     for (int n = 0; n < NI; ++n) f.p[n] += step;
 }
 
+// The same fill addressed as a wave-uniform tile base (scalar registers, stepped once per tile)
+// plus a per-lane 32-bit byte offset that never changes: half the address registers of
+// TileStream and no per-tile vector adds.  Needs 64 rows of the view to span < 4 GiB.
+template <int NW>
+struct TileOffsets {
+    static constexpr int kInstr = 16 / NW;
+    uint32_t off[16 / NW];
+};
+
+template <int NW>
+__device__ __forceinline__ TileOffsets<NW> make_tile_offsets(int64_t ss, int wave, int lane)
+{
+    TileOffsets<NW> f;
+#pragma unroll
+    for (int n = 0; n < TileOffsets<NW>::kInstr; ++n) {
+        const int row = 4 * (TileOffsets<NW>::kInstr * wave + n) + (lane >> 4);
+        const int chunk = (lane & 15) ^ swz(row);
+        f.off[n] = (uint32_t)(row * ss * 2 + chunk * 16);
+    }
+    return f;
+}
+
+// instruction n of the fill of the full tile whose first row is at `tile_base`
+template <int NW>
+__device__ __forceinline__ void fill_full_tile_part(LDS_AS unsigned char *tile, const TileOffsets<NW> &f, int n,
+                                                    const char *tile_base, int wave)
+{
+    __builtin_amdgcn_global_load_lds((const GLB_AS void *)(tile_base + f.off[n]),
+                                     (LDS_AS void *)(tile + (TileOffsets<NW>::kInstr * wave + n) * 1024), 16, 0, 0);
+}
+
+// the ragged last tile: rows past S re-read row S-1 (finite values; every consumer masks them)
+template <int NW>
+__device__ __forceinline__ void fill_ragged_tile(LDS_AS unsigned char *tile, const __bf16 *src, int64_t ss,
+                                                 int64_t r0, int64_t S, int wave, int lane)
+{
+    constexpr int NI = 16 / NW;
+#pragma unroll
+    for (int n = 0; n < NI; ++n) {
+        const int row = 4 * (NI * wave + n) + (lane >> 4);
+        const int chunk = (lane & 15) ^ swz(row);
+        int64_t rg = r0 + row;
+        rg = rg < S ? rg : S - 1;
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(src + rg * ss + chunk * 8),
+                                         (LDS_AS void *)(tile + (NI * wave + n) * 1024), 16, 0, 0);
+    }
+}
+
 // ---- software-pipelined LDS operand reads ---------------------------------------------------
 // The compiler issues an LDS read right before the MFMA that consumes it and then waits for ALL
 // outstanding LDS traffic, which exposes the full LDS latency once per MFMA.  The operand reads of
@@ -581,34 +629,42 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_bwd_dq_bf16_kernel(AttnAr
     }
 }
 
-// ============================================================================ backward: dK, dV
-// Workgroup: 8 waves, 128 key rows; queries streamed in tiles of 64 from the diagonal to the
-// end of the sequence.  Waves w and w+4 form a pair owning key rows 32w..32w+31 and split the
-// four contractions so that each keeps only one 32x128 fp32 accumulator set (two waves per
-// SIMD fit the register file, and the exponentials of one wave overlap the MFMAs of the other):
-//   V-wave (w < 4):  S = Q K^T -> P = exp(S - LSE_i)            | dV^T += dO^T P
-//   K-wave (w >= 4): dP = dO V^T                                 | dS = P (dP - D_i), dK^T += Q^T dS
-// P (fp32) passes from the V-wave to the K-wave through LDS as a register image: both waves
-// hold key j in lane j, so lane l of the K-wave reads back exactly what lane l of the V-wave
-// wrote.  A mid-tile barrier separates the two halves.  No atomics: each key row has one owner.
 constexpr int kBwdBk = 128, kBq = 64;
+
+// ============================================================================ backward: dK, dV
+// Workgroup: 8 waves, 128 key rows whose K and V stay in LDS for the workgroup's lifetime;
+// queries streamed in tiles of 64 through the double-buffered ring (one barrier per tile).
+// Wave w owns the 32 x 32 block (queries 32*(w/4).., keys 32*(w%4)..) of every tile and runs
+// all four contractions on it, so nothing passes between waves inside the loop:
+//   S = Q K^T, dP = dO V^T (both operands from LDS, the two accumulation chains interleaved)
+//   P = exp(S - LSE_i), dS = P (dP - D_i)         (lane = key, 16 query rows per lane)
+//   dV^T += dO^T P,  dK^T += Q^T dS                (transposed LDS reads, P / dS from registers)
+// Waves w and w+4 hold partial sums for the same keys over disjoint queries; they are added
+// through LDS once, after the loop (wave w finishes dV, wave w+4 finishes dK).  No atomics.
+struct PairSlot { bf16x8 a, b; };
+
+template <int N>
+__device__ __forceinline__ void lds_wait(PairSlot &x)
+{
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x.a), "+v"(x.b) : "n"(N));
+}
 
 __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
 {
-    // [buf][Q|dO] tiles, P exchange (4 pairs x 2 blocks x 64 lanes x 64 B), [buf][LSE*log2e | D] rows
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes + 32768 + 1024];
+    constexpr int kKsOff = 4 * kTileBytes, kVsOff = 6 * kTileBytes, kStatOff = 8 * kTileBytes;
+    // [buf][Q|dO] ring, K rows, V rows (128 x 256 B each), [buf][LSE*log2e | D] rows
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[8 * kTileBytes + 1024];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
-    LDS_AS unsigned char *Px = lds + 4 * kTileBytes;
-    LDS_AS float *Stat = (LDS_AS float *)(Px + 32768);      // [buf][2][64]
+    LDS_AS float *Stat = (LDS_AS float *)(lds + kStatOff);      // [buf][2][64]
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
-    const int pair = wave & 3;
-    const bool v_role = wave < 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kb = wave & 3, qh = wave >> 2;
     const LaneAddr la = make_lane_addr(lane);
     const int64_t nkt = (a.S + kBwdBk - 1) / kBwdBk;
     const TileId t = decode_block(a, nkt, false);     // key tile 0 sees every query: heaviest first
-    const int64_t col0 = t.tile * kBwdBk, j0w = col0 + 32 * pair, j = j0w + l32;
+    const int64_t col0 = t.tile * kBwdBk, j0w = col0 + 32 * kb, j = j0w + l32;
     const int64_t base = (int64_t)t.b * a.sb + (int64_t)t.h * a.sh;
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
@@ -616,48 +672,59 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
 
     const int it0 = (int)(col0 / kBq);
     const int nit = (int)((a.S + kBq - 1) / kBq);
-    TileStream<8> qs = make_tile_stream<8>(q, a.ss, (int64_t)it0 * kBq, wave, lane);
-    TileStream<8> gs = make_tile_stream<8>(g, a.ss, (int64_t)it0 * kBq, wave, lane);
-    fill_tile_async(lds, qs, q, a.ss, (int64_t)it0 * kBq, a.S, wave, lane);
-    fill_tile_async(lds + kTileBytes, gs, g, a.ss, (int64_t)it0 * kBq, a.S, wave, lane);
-
-    // this wave's resident B operand: K rows (V-wave) or V rows (K-wave); lane = key j
-    bf16x8 wB[8];
-    {
-        const __bf16 *src = static_cast<const __bf16 *>(v_role ? a.k : a.v) + base;
-        const int64_t jq = j < a.S ? j : a.S - 1;     // keys past S are computed and never stored
-#pragma unroll
-        for (int kc = 0; kc < 8; ++kc)
-            wB[kc] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(src + jq * a.ss + 16 * kc + 8 * half));
+    {   // resident K and V rows of this key tile (rows past S repeat row S-1, never stored)
+        const __bf16 *kp = static_cast<const __bf16 *>(a.k) + base;
+        const __bf16 *vp = static_cast<const __bf16 *>(a.v) + base;
+        TileStream<8> ks = make_tile_stream<8>(kp, a.ss, col0, wave, lane);
+        TileStream<8> vs = make_tile_stream<8>(vp, a.ss, col0, wave, lane);
+        fill_tile_async(lds + kKsOff, ks, kp, a.ss, col0, a.S, wave, lane);
+        fill_tile_async(lds + kKsOff + kTileBytes, ks, kp, a.ss, col0 + 64, a.S, wave, lane);
+        fill_tile_async(lds + kVsOff, vs, vp, a.ss, col0, a.S, wave, lane);
+        fill_tile_async(lds + kVsOff + kTileBytes, vs, vp, a.ss, col0 + 64, a.S, wave, lane);
     }
+    const TileOffsets<8> toff = make_tile_offsets<8>(a.ss, wave, lane);
+    const int64_t tile_step_bytes = kBq * a.ss * 2;
+    auto fill_tile = [&](LDS_AS unsigned char *dst, const __bf16 *src, int64_t r0) {
+        if (r0 + kBq <= a.S) {
+            const char *tb = reinterpret_cast<const char *>(src) + (r0 / kBq) * tile_step_bytes;
+            fill_full_tile_part(dst, toff, 0, tb, wave);
+            fill_full_tile_part(dst, toff, 1, tb, wave);
+        } else {
+            fill_ragged_tile<8>(dst, src, a.ss, r0, a.S, wave, lane);
+        }
+    };
+    fill_tile(lds, q, (int64_t)it0 * kBq);
+    fill_tile(lds + kTileBytes, g, (int64_t)it0 * kBq);
+
     const float c = a.scale * kLog2e;
-    f32x16 acc[4];                                    // dV^T (V-wave) or dK^T (K-wave)
+    f32x16 accV[4], accK[4];                          // dV^T, dK^T: lane = key, rows = head dim
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[cb][e] = 0.f;
+        for (int e = 0; e < 16; ++e) accV[cb][e] = accK[cb][e] = 0.f;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // per-row statistics of a query tile: threads 0..63 LSE*log2e, threads 64..127 D_i.
     // rows past S: LSE = +inf makes their probabilities exactly zero
+    // The value is loaded raw and only scaled when it is written to LDS a tile later, so that
+    // nothing waits for the load (and for the fills queued before it) right after issuing it.
+    const float *stat_src = (tid < 64 ? a.lse : a.delta) + stat;
+    const float stat_pad = tid < 64 ? INFINITY : 0.f, stat_mul = tid < 64 ? kLog2e : 1.f;
     auto load_stat = [&](int it) -> float {
-        if (tid >= 128) return 0.f;
         const int64_t r = (int64_t)it * kBq + (tid & 63);
-        if (tid < 64) return r < a.S ? a.lse[stat + r] * kLog2e : INFINITY;
-        return r < a.S ? a.delta[stat + r] : 0.f;
+        return (tid < 128 && r < a.S) ? stat_src[r] : stat_pad;
     };
     float sreg = load_stat(it0);
-    if (tid < 128) Stat[tid] = sreg;
-    LDS_AS unsigned char *Pw = Px + pair * 8192 + lane * 16;   // + ib*4096 + 1024*(e/4)
+    if (tid < 128) Stat[tid] = sreg * stat_mul;
 
     const LdsAddr ad = make_lds_addr(lds, la);
     const uint32_t (&row_addr)[8] = ad.row;
     const uint32_t (&tr_addr)[4][2] = ad.tr;
+    // this wave's rows of the resident operands and of the ring tiles
+    uint32_t kv_addr[8];
+#pragma unroll
+    for (int kc = 0; kc < 8; ++kc) kv_addr[kc] = row_addr[kc] + (uint32_t)(kKsOff + kb * 8192);
 
-    // The two roles run separate copies of the loop (the role is a compile-time constant inside),
-    // with identical barrier sequences.
-    auto role_loop = [&](auto rolec) {
-    constexpr bool VR = decltype(rolec)::value;
     auto tile_step = [&](auto bufc, int it) {
         constexpr int BUF = decltype(bufc)::value;
         constexpr int qOff = BUF * 2 * kTileBytes, gOff = qOff + kTileBytes;
@@ -665,138 +732,114 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
         const LDS_AS float *Ls = Stat + BUF * 128, *Ds = Ls + 64;
         wait_fills();
         __syncthreads();          // tile `it` and its statistics are complete; the other buffers are free
-        if (it + 1 < nit) {
-            fill_tile_async(lds + nOff, qs, q, a.ss, (int64_t)(it + 1) * kBq, a.S, wave, lane);
-            fill_tile_async(lds + nOff + kTileBytes, gs, g, a.ss, (int64_t)(it + 1) * kBq, a.S, wave, lane);
-            sreg = load_stat(it + 1);
+        const bool more = it + 1 < nit;
+        const int64_t rn = (int64_t)(it + 1) * kBq;
+        if (more) sreg = load_stat(it + 1);
+        // the four fill instructions of the next tile, queued one at a time between the MFMAs
+        const int64_t i0 = (int64_t)it * kBq + 32 * qh;           // first query of this wave's block
+        const bool active = i0 + 31 >= j0w;           // else all 32 queries precede this wave's keys
+        // A full next tile is fetched by four fill instructions queued one at a time between the
+        // MFMAs below; the ragged last tile (and a wave with nothing to compute) queues them here.
+        const bool spread = more && active && rn + kBq <= a.S;
+        if (more && !spread) {
+            fill_tile(lds + nOff, q, rn);
+            fill_tile(lds + nOff + kTileBytes, g, rn);
         }
-        const int64_t i0 = (int64_t)it * kBq;
-        const bool active = i0 + kBq - 1 >= j0w;      // else all 64 queries precede this pair's keys
-        const bool diag = i0 < j0w + 31;
-        const int thr = (int)(j - i0) - 4 * half;     // query offset e' is visible iff e' >= thr
-        bf16x8 pB[4];                                 // V-wave: P chunks [2*ib + sub]
-        f32x16 dp[2];                                 // K-wave: dP blocks
-        TrSlot tring[4];                              // transposed operands of the second half
-        // second half: item n = (qi = n/4, cb = n%4), A = dO^T (V-wave) or Q^T (K-wave)
-        auto t_issue = [&](auto n, TrSlot &slot) {
-            constexpr int qi = decltype(n)::value / 4, cb = decltype(n)::value % 4;
-            lds_issue_tr<qi * 4096 + (VR ? gOff : qOff)>(slot, tr_addr[cb][0], tr_addr[cb][1]);
+        const char *nq = reinterpret_cast<const char *>(q) + (int64_t)(it + 1) * tile_step_bytes;
+        const char *ng = reinterpret_cast<const char *>(g) + (int64_t)(it + 1) * tile_step_bytes;
+        auto fill_part = [&](auto pc) {
+            constexpr int part = decltype(pc)::value;
+            if (!spread) return;
+            fill_full_tile_part(lds + nOff + (part / 2) * kTileBytes, toff, part % 2, part < 2 ? nq : ng, wave);
         };
-
-        // V-wave: scores and probabilities of one 32-query block; P goes to the K-wave through LDS
-        auto v_scores = [&](auto ibc) {
-            constexpr int ib = decltype(ibc)::value;
-            f32x16 s;
+        if (active) {
+            const bool diag = i0 < j0w + 31;
+            const int thr = (int)(j - i0) - 4 * half; // query offset e' is visible iff e' >= thr
+            f32x16 s, dp;
             {
-                bf16x8 ring[5];
-                auto issue = [&](auto n, bf16x8 &slot) {
-                    lds_issue_b128<ib * 8192 + qOff>(slot, row_addr[decltype(n)::value]);
+                // item n: k-chunk n/2 of S (even n: Q rows x K rows) or of dP (odd n: dO rows x V rows)
+                PairSlot ring[3];
+                auto issue = [&](auto n, PairSlot &slot) {
+                    constexpr int kc = decltype(n)::value / 2, which = decltype(n)::value % 2;
+                    lds_issue_b128<(which ? gOff : qOff)>(slot.a, row_addr[kc] + (uint32_t)(qh * 8192));
+                    lds_issue_b128<(which ? kVsOff - kKsOff : 0)>(slot.b, kv_addr[kc]);
                 };
-                lds_pipeline_prologue<8, 4, 1>(ring, issue);
-                lds_pipeline_body<8, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
-                    constexpr int kc = decltype(n)::value;
-                    s = mfma32(slot, wB[kc], kc == 0 ? zero : s);
+                lds_pipeline_prologue<16, 2, 2>(ring, issue);
+                lds_pipeline_body<16, 2, 2>(ring, issue, [&](auto n, PairSlot &slot) {
+                    constexpr int kc = decltype(n)::value / 2, which = decltype(n)::value % 2;
+                    if constexpr (which == 0) s = mfma32(slot.a, slot.b, kc == 0 ? zero : s);
+                    else dp = mfma32(slot.a, slot.b, kc == 0 ? zero : dp);
+                    if constexpr (decltype(n)::value % 4 == 1) fill_part(IntC<decltype(n)::value / 4>{});
                 });
             }
-            // s: lane = key j, register e = query row 32*ib + 8*(e/4) + 4*half + e%4
+            // item n < 8: dV^T block (sub = n/4, cb = n%4), A = dO^T; n >= 8: dK^T, A = Q^T
+            TrSlot tring[3];
+            auto t_issue = [&](auto n, TrSlot &slot) {
+                constexpr int m = decltype(n)::value % 8, sub = m / 4, cb = m % 4;
+                constexpr int off = (decltype(n)::value < 8 ? gOff : qOff) + sub * 4096;
+                lds_issue_tr<off>(slot, tr_addr[cb][0] + (uint32_t)(qh * 8192), tr_addr[cb][1] + (uint32_t)(qh * 8192));
+            };
+            lds_pipeline_prologue<16, 2, 2>(tring, t_issue);
+            // s, dp: lane = key j, register e = query row i0 + 8*(e/4) + 4*half + e%4
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * ib + 8 * gq + 4 * half);
+                const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * qh + 8 * gq + 4 * half);
+                const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * qh + 8 * gq + 4 * half);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int e = 4 * gq + r;
                     float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[r]));
-                    if (diag && (32 * ib + 8 * gq + r < thr)) p = 0.f;
+                    if (diag && (8 * gq + r < thr)) p = 0.f;
                     s[e] = p;
+                    dp[e] = p * (dp[e] - d4[r]);
                 }
             }
-            pB[2 * ib] = pack8(s, 0);
-            pB[2 * ib + 1] = pack8(s, 8);
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 p4 = {s[4 * gq], s[4 * gq + 1], s[4 * gq + 2], s[4 * gq + 3]};
-                *reinterpret_cast<LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024) = p4;
-            }
-        };
-        // K-wave: dS of one 32-query block from the V-wave's P, then dK^T += Q^T dS over that block
-        auto k_block = [&](auto ibc) {
-            constexpr int ib = decltype(ibc)::value;
-            TrSlot ring[4];
-            auto issue = [&](auto n, TrSlot &slot) {
-                constexpr int qi = 2 * ib + decltype(n)::value / 4, cb = decltype(n)::value % 4;
-                lds_issue_tr<qi * 4096 + qOff>(slot, tr_addr[cb][0], tr_addr[cb][1]);
-            };
-            lds_pipeline_prologue<8, 3, 2>(ring, issue);
-            f32x16 ds;
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                // registers 4*gq + r of the block = query rows 32*ib + 8*gq + 4*half + r
-                const f32x4 p4 = *reinterpret_cast<const LDS_AS f32x4 *>(Pw + ib * 4096 + gq * 1024);
-                const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * ib + 8 * gq + 4 * half);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) ds[4 * gq + r] = p4[r] * (dp[ib][4 * gq + r] - d4[r]);
-            }
-            bf16x8 dsB[2];
-            dsB[0] = pack8(ds, 0);
-            dsB[1] = pack8(ds, 8);
-            lds_pipeline_body<8, 3, 2>(ring, issue, [&](auto n, TrSlot &slot) {
-                constexpr int sub = decltype(n)::value / 4, cb = decltype(n)::value % 4;
-                acc[cb] = mfma32(tr_operand(slot), dsB[sub], acc[cb]);
+            bf16x8 pB[2], dsB[2];
+            pB[0] = pack8(s, 0);
+            pB[1] = pack8(s, 8);
+            dsB[0] = pack8(dp, 0);
+            dsB[1] = pack8(dp, 8);
+            lds_pipeline_body<16, 2, 2>(tring, t_issue, [&](auto n, TrSlot &slot) {
+                constexpr int m = decltype(n)::value % 8, sub = m / 4, cb = m % 4;
+                if constexpr (decltype(n)::value < 8) accV[cb] = mfma32(tr_operand(slot), pB[sub], accV[cb]);
+                else accK[cb] = mfma32(tr_operand(slot), dsB[sub], accK[cb]);
             });
-        };
-
-        // Three intervals per tile, so that in each of them both waves of a pair have MFMA work
-        // and the exponentials / dS arithmetic of one overlap the MFMAs of the other:
-        //   1: V scores+P(block 0)      | K dP(blocks 0,1)
-        //   2: V scores+P(block 1)      | K dS,dK(block 0)
-        //   3: V dV(blocks 0,1)         | K dS,dK(block 1)
-        if (active) {
-            if constexpr (VR) {
-                v_scores(IntC<0>{});
-            } else {
-                static_for<0, 2>([&](auto ibc) {
-                    constexpr int ib = decltype(ibc)::value;
-                    bf16x8 ring[5];
-                    auto issue = [&](auto n, bf16x8 &slot) {
-                        lds_issue_b128<ib * 8192 + gOff>(slot, row_addr[decltype(n)::value]);
-                    };
-                    lds_pipeline_prologue<8, 4, 1>(ring, issue);
-                    lds_pipeline_body<8, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
-                        constexpr int kc = decltype(n)::value;
-                        dp[ib] = mfma32(slot, wB[kc], kc == 0 ? zero : dp[ib]);
-                    });
-                });
-            }
         }
-        __syncthreads();          // P of block 0 is in LDS
-        if (active) {
-            if constexpr (VR) v_scores(IntC<1>{});
-            else k_block(IntC<0>{});
-        }
-        __syncthreads();          // P of block 1 is in LDS
-        if (active) {
-            if constexpr (VR) {
-                lds_pipeline_prologue<16, 3, 2>(tring, t_issue);
-                lds_pipeline_body<16, 3, 2>(tring, t_issue, [&](auto n, TrSlot &slot) {
-                    constexpr int qi = decltype(n)::value / 4, cb = decltype(n)::value % 4;
-                    acc[cb] = mfma32(tr_operand(slot), pB[qi], acc[cb]);
-                });
-            } else {
-                k_block(IntC<1>{});
-            }
-        }
-        if (it + 1 < nit && tid < 128) Stat[(BUF ^ 1) * 128 + tid] = sreg;
+        if (more && tid < 128) Stat[(BUF ^ 1) * 128 + tid] = sreg * stat_mul;
     };
     for (int it = it0; it < nit; it += 2) {
         tile_step(IntC<0>{}, it);
         if (it + 1 < nit) tile_step(IntC<1>{}, it + 1);
     }
-    };
-    if (v_role) role_loop(IntC<1>{});
-    else role_loop(IntC<0>{});
-    if (j < a.S) {
-        __bf16 *out = static_cast<__bf16 *>(v_role ? a.dv : a.dk) + base + j * a.ss;
-        store_acc_T(out, acc, v_role ? 1.f : a.scale, half);
+
+    // Add the two query halves: wave (kb, 0) hands its dK^T to wave (kb, 1) and takes that
+    // wave's dV^T, as register images (lane l reads what lane l of the partner wrote).
+    __syncthreads();              // every wave is done with the tiles
+    {
+        LDS_AS f32x4 *mine = (LDS_AS f32x4 *)lds + (size_t)wave * 1024 + lane;          // 16 KB per wave
+        LDS_AS f32x4 *theirs = (LDS_AS f32x4 *)lds + (size_t)(wave ^ 4) * 1024 + lane;
+        f32x16 (&give)[4] = qh == 0 ? accK : accV;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 x = {give[cb][4 * gq], give[cb][4 * gq + 1], give[cb][4 * gq + 2], give[cb][4 * gq + 3]};
+                mine[(cb * 4 + gq) * 64] = x;
+            }
+        __syncthreads();
+        f32x16 (&keep)[4] = qh == 0 ? accV : accK;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 x = theirs[(cb * 4 + gq) * 64];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) keep[cb][4 * gq + r] += x[r];
+            }
+        if (j < a.S) {
+            __bf16 *out = static_cast<__bf16 *>(qh == 0 ? a.dv : a.dk) + base + j * a.ss;
+            store_acc_T(out, keep, qh == 0 ? 1.f : a.scale, half);
+        }
     }
 }
 
