@@ -30,9 +30,9 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # figures are carried here per workload; a workload that was not profiled reports null.
 GIB = float(1 << 30)
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "C5": {"attn_fwd_bf16_kernel": (418.7 + 1.02) * GIB,
-           "attn_bwd_dkdv_bf16_kernel": (270.3 + 2.00) * GIB,
-           "attn_bwd_dq_bf16_kernel": (731.8 + 1.00) * GIB},
+    "C5": {"attn_fwd_bf16_kernel": (413.0 + 1.02) * GIB,
+           "attn_bwd_dkdv_bf16_kernel": (872.9 + 2.00) * GIB,
+           "attn_bwd_dq_bf16_kernel": (771.9 + 1.00) * GIB},
 }
 
 
