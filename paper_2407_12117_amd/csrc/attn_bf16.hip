@@ -436,24 +436,24 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
         // item n = (jb = n/8, kc = n%8): one row operand of K, read 4 MFMAs ahead
         f32x16 s[2];
         {
-            bf16x8 ring[5];
+            bf16x8 ring[3];
             auto issue = [&](auto n, bf16x8 &slot) {
                 constexpr int jb = decltype(n)::value / 8, kc = decltype(n)::value % 8;
                 lds_issue_b128<jb * 8192 + kOff>(slot, row_addr[kc]);
             };
-            lds_pipeline_prologue<16, 4, 1>(ring, issue);
-            lds_pipeline_body<16, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
+            lds_pipeline_prologue<16, 2, 1>(ring, issue);
+            lds_pipeline_body<16, 2, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
                 constexpr int jb = decltype(n)::value / 8, kc = decltype(n)::value % 8;
                 s[jb] = mfma32(slot, qB[kc], kc == 0 ? zero : s[jb]);
             });
         }
         // the first V^T operands are requested now: their latency hides behind the softmax
-        TrSlot vring[4];
+        TrSlot vring[3];
         auto v_issue = [&](auto n, TrSlot &slot) {
             constexpr int kj = decltype(n)::value / 4, cb = decltype(n)::value % 4;
             lds_issue_tr<kj * 4096 + vOff>(slot, tr_addr[cb][0], tr_addr[cb][1]);
         };
-        lds_pipeline_prologue<16, 3, 2>(vring, v_issue);
+        lds_pipeline_prologue<16, 2, 2>(vring, v_issue);
         if (jt >= wave_first_diag) {                  // diagonal tile: mask keys j > i
             const int thr = (int)(i - (int64_t)jt * kBk) - 4 * half;    // key offset e' is visible iff e' <= thr
 #pragma unroll
@@ -494,7 +494,7 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
         bf16x8 pB[4];
 #pragma unroll
         for (int kj = 0; kj < 4; ++kj) pB[kj] = pack8(s[kj >> 1], 8 * (kj & 1));
-        lds_pipeline_body<16, 3, 2>(vring, v_issue, [&](auto n, TrSlot &slot) {
+        lds_pipeline_body<16, 2, 2>(vring, v_issue, [&](auto n, TrSlot &slot) {
             constexpr int kj = decltype(n)::value / 4, cb = decltype(n)::value % 4;
             accO[cb] = mfma32(tr_operand(slot), pB[kj], accO[cb]);
         });
