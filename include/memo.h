@@ -224,6 +224,30 @@ void *memo_sched_buffer(const memo_sched *s, int32_t layer);
 /* Waits for nothing: the caller synchronises its streams first.  NULL is accepted. */
 memo_status memo_sched_destroy(memo_sched *s);
 
+/*
+ * Token-wise recomputation of the tensors that follow the stored layer input (Section 4.1:
+ * the layer input is kept whole so that "input_norm", "q", "k", "v" can be rebuilt; the
+ * swapped rows [0,k) come back from the host, the dropped rows [k,S) are recomputed).
+ * Both operations work on a row range of token-major bf16 tensors and each output row
+ * depends on its own input row only, computed in a fixed order: a row recomputed in any
+ * range is bit-identical to the same row of a pass over all rows.
+ *
+ * memo_layernorm_rows:  y[r,:] = (x[r,:] - mean_r) / sqrt(var_r + eps) * gamma + beta for
+ *   row_begin <= r < row_end; x, y device [S,h] bf16 contiguous, gamma, beta device [h] bf16;
+ *   statistics in fp32 (biased variance).  h a multiple of 512, at most 8192.
+ * memo_linear_rows:     out[r,:] = a[r,:] * w^T + bias for the same kind of range; a device
+ *   [S,K] bf16, w device [N,K] bf16 (K contiguous), bias device [N] bf16 or NULL, out device
+ *   [S,N] bf16; fp32 accumulation on the matrix cores.  K and N multiples of 128.
+ * All pointers 16-byte aligned.  An empty range queues nothing.  Rows outside the range are
+ * neither read nor written.  MEMO_ERR_INVALID_ARG / MEMO_ERR_UNSUPPORTED before any launch.
+ */
+memo_status memo_layernorm_rows(const void *x, const void *gamma, const void *beta, void *y,
+                                int64_t S, int32_t h, float eps, int64_t row_begin,
+                                int64_t row_end, void *hip_stream);
+memo_status memo_linear_rows(const void *a, const void *w, const void *bias, void *out, int64_t S,
+                             int32_t K, int32_t N, int64_t row_begin, int64_t row_end,
+                             void *hip_stream);
+
 /* Pinned host memory helpers (hipHostMalloc / hipHostFree). */
 memo_status memo_host_alloc(void **host_ptr, size_t bytes);
 memo_status memo_host_free(void *host_ptr);

@@ -29,6 +29,7 @@ EXPORTS = [
     "memo_buffer_plan_make", "memo_sched_create", "memo_sched_forward_begin",
     "memo_sched_forward_end", "memo_sched_backward_begin", "memo_sched_backward_end",
     "memo_sched_buffer", "memo_sched_destroy",
+    "memo_layernorm_rows", "memo_linear_rows",
 ]
 
 
@@ -117,6 +118,10 @@ def lib():
     L.memo_sched_buffer.restype = vp
     L.memo_sched_destroy.argtypes = [vp]
     L.memo_sched_destroy.restype = ctypes.c_int
+    L.memo_layernorm_rows.argtypes = [vp, vp, vp, vp, i64, ctypes.c_int32, ctypes.c_float, i64, i64, vp]
+    L.memo_layernorm_rows.restype = ctypes.c_int
+    L.memo_linear_rows.argtypes = [vp, vp, vp, vp, i64, ctypes.c_int32, ctypes.c_int32, i64, i64, vp]
+    L.memo_linear_rows.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -357,3 +362,55 @@ class MemoSched:
             self.destroy()
         except Exception:
             pass
+
+
+def _row_range(rows, S):
+    if rows is None:
+        return 0, S
+    b, e = rows
+    return int(b), int(e)
+
+
+def _bf16_2d(t, name):
+    if t.dtype != torch.bfloat16 or t.dim() != 2 or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous 2-D bf16 tensor")
+
+
+def memo_layernorm_rows(x, gamma, beta, eps, y=None, rows=None, stream=None):
+    """y[r] = LayerNorm(x[r]) * gamma + beta for r in rows = (begin, end) (default: all rows).
+    x, y: [S,h] bf16; other rows of y are left as they are."""
+    _bf16_2d(x, "x")
+    S, h = x.shape
+    if y is None:
+        y = torch.empty_like(x)
+    _bf16_2d(y, "y")
+    if y.shape != x.shape or gamma.shape != (h,) or beta.shape != (h,):
+        raise ValueError("shape mismatch")
+    if gamma.dtype != torch.bfloat16 or beta.dtype != torch.bfloat16:
+        raise ValueError("gamma, beta must be bf16")
+    b, e = _row_range(rows, S)
+    _check(lib().memo_layernorm_rows(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), y.data_ptr(), S, h,
+                                     float(eps), b, e, _stream_ptr(stream)), "memo_layernorm_rows")
+    return y
+
+
+def memo_linear_rows(a, w, bias=None, out=None, rows=None, stream=None):
+    """out[r] = a[r] @ w.T + bias for r in rows = (begin, end) (default: all rows).
+    a: [S,K] bf16, w: [N,K] bf16, bias: [N] bf16 or None, out: [S,N] bf16."""
+    _bf16_2d(a, "a")
+    _bf16_2d(w, "w")
+    S, K = a.shape
+    N = w.shape[0]
+    if w.shape[1] != K:
+        raise ValueError("w must be [N,K]")
+    if out is None:
+        out = torch.empty((S, N), dtype=torch.bfloat16, device=a.device)
+    _bf16_2d(out, "out")
+    if tuple(out.shape) != (S, N):
+        raise ValueError("out must be [S,N]")
+    if bias is not None and (bias.dtype != torch.bfloat16 or tuple(bias.shape) != (N,)):
+        raise ValueError("bias must be bf16 [N]")
+    b, e = _row_range(rows, S)
+    _check(lib().memo_linear_rows(a.data_ptr(), w.data_ptr(), None if bias is None else bias.data_ptr(),
+                                  out.data_ptr(), S, K, N, b, e, _stream_ptr(stream)), "memo_linear_rows")
+    return out

@@ -233,6 +233,33 @@ memo_status memo_solve_alpha(double s_in, double s_attn, double s_oth, double ba
     return MEMO_OK;
 }
 
+memo_status memo_layernorm_rows(const void *x, const void *gamma, const void *beta, void *y,
+                                int64_t S, int32_t h, float eps, int64_t row_begin,
+                                int64_t row_end, void *hip_stream)
+{
+    if (!x || !gamma || !beta || !y || S < 1) return MEMO_ERR_INVALID_ARG;
+    if (row_begin < 0 || row_end < row_begin || row_end > S) return MEMO_ERR_INVALID_ARG;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return MEMO_ERR_INVALID_ARG;
+    if (h < 512 || h > 8192 || h % 512) return MEMO_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y)) return MEMO_ERR_UNSUPPORTED;
+    const hipError_t e = memo::launch_layernorm_rows_bf16(x, gamma, beta, y, row_begin, row_end, h, eps,
+                                                          static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MEMO_OK : MEMO_ERR_DEVICE;
+}
+
+memo_status memo_linear_rows(const void *a, const void *w, const void *bias, void *out, int64_t S,
+                             int32_t K, int32_t N, int64_t row_begin, int64_t row_end,
+                             void *hip_stream)
+{
+    if (!a || !w || !out || S < 1) return MEMO_ERR_INVALID_ARG;
+    if (row_begin < 0 || row_end < row_begin || row_end > S) return MEMO_ERR_INVALID_ARG;
+    if (K < 128 || N < 128 || K % 128 || N % 128) return MEMO_ERR_UNSUPPORTED;
+    if (!aligned16(a) || !aligned16(w) || !aligned16(out) || (bias && !aligned16(bias))) return MEMO_ERR_UNSUPPORTED;
+    const hipError_t e = memo::launch_linear_rows_bf16(a, w, bias, out, row_begin, row_end, K, N,
+                                                       static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MEMO_OK : MEMO_ERR_DEVICE;
+}
+
 memo_status memo_host_alloc(void **host_ptr, size_t bytes)
 {
     if (!host_ptr || bytes == 0) return MEMO_ERR_INVALID_ARG;

@@ -39,4 +39,11 @@ hipError_t launch_attn_bwd_bf16(const AttnArgs &a, hipStream_t st);
 // D_i = sum_c dO_ic * O_ic for either dtype (is_bf16 selects the element type)
 hipError_t launch_attn_delta(const AttnArgs &a, bool is_bf16, hipStream_t st);
 
+// Token-wise recomputation (bf16): LayerNorm of rows [row_begin,row_end) of x [S,h] and the
+// projection out[rows, N] = a[rows, K] * w[N, K]^T + bias over the same kind of row range.
+hipError_t launch_layernorm_rows_bf16(const void *x, const void *gamma, const void *beta, void *y,
+                                      int64_t row_begin, int64_t row_end, int h, float eps, hipStream_t st);
+hipError_t launch_linear_rows_bf16(const void *a, const void *w, const void *bias, void *out,
+                                   int64_t row_begin, int64_t row_end, int K, int N, hipStream_t st);
+
 }  // namespace memo

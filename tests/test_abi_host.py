@@ -204,3 +204,30 @@ def test_buffer_plan_and_sched_reject_bad_arguments():
     assert L.memo_sched_backward_end(None, 0) == mb.MEMO_ERR_INVALID_ARG
     assert L.memo_sched_buffer(None, 0) is None
     assert L.memo_sched_destroy(None) == mb.MEMO_OK
+
+
+# ------------------------------------------- token-wise recomputation (Section 4.1)
+def test_recompute_entry_points_reject_bad_arguments():
+    L = mb.lib()
+    ok = ctypes.c_void_p(4096)
+    odd = ctypes.c_void_p(4100)
+    ln = lambda x=ok, g=ok, b=ok, y=ok, S=64, h=4096, eps=1e-5, r0=0, r1=64: \
+        L.memo_layernorm_rows(x, g, b, y, S, h, eps, r0, r1, None)
+    assert ln(x=None) == mb.MEMO_ERR_INVALID_ARG
+    assert ln(r0=-1) == mb.MEMO_ERR_INVALID_ARG
+    assert ln(r0=10, r1=9) == mb.MEMO_ERR_INVALID_ARG
+    assert ln(r1=65) == mb.MEMO_ERR_INVALID_ARG
+    assert ln(eps=-1.0) == mb.MEMO_ERR_INVALID_ARG
+    assert ln(eps=float("nan")) == mb.MEMO_ERR_INVALID_ARG
+    assert ln(h=4000) == mb.MEMO_ERR_UNSUPPORTED
+    assert ln(h=16384) == mb.MEMO_ERR_UNSUPPORTED
+    assert ln(y=odd) == mb.MEMO_ERR_UNSUPPORTED
+    assert ln(r0=7, r1=7) == mb.MEMO_OK                      # empty range: nothing queued
+    lin = lambda a=ok, w=ok, bias=None, out=ok, S=64, K=4096, N=1536, r0=0, r1=64: \
+        L.memo_linear_rows(a, w, bias, out, S, K, N, r0, r1, None)
+    assert lin(w=None) == mb.MEMO_ERR_INVALID_ARG
+    assert lin(r1=100) == mb.MEMO_ERR_INVALID_ARG
+    assert lin(K=100) == mb.MEMO_ERR_UNSUPPORTED
+    assert lin(N=1500) == mb.MEMO_ERR_UNSUPPORTED
+    assert lin(bias=odd) == mb.MEMO_ERR_UNSUPPORTED
+    assert lin(r0=64, r1=64) == mb.MEMO_OK
