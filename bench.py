@@ -81,6 +81,9 @@ def main():
                     help="instead of the default step: run the two-rounding-buffer schedule over "
                          "--layers stand-in layers at these sequence lengths and report the exposed "
                          "copy time per alpha")
+    ap.add_argument("--recompute", default=None, metavar="S",
+                    help="instead of the default step: time the token-wise recomputation kernels "
+                         "(LayerNorm h=4096 and the 4096 -> 1536 projection) on rows [k,S) per alpha")
     ap.add_argument("--layers", type=int, default=6)
     ap.add_argument("--alphas", default="0,0.25,0.5,0.75,1")
     args = ap.parse_args()
@@ -98,6 +101,9 @@ def main():
     torch.cuda.set_device(0)
     if args.schedule:
         schedule_bench(torch, mb, synth, args)
+        return
+    if args.recompute:
+        recompute_bench(torch, mb, args)
         return
     cfg = synth.CONFIGS[args.config]
     assert cfg["dtype"] == "bf16", "bench workloads are the bf16 ones (C2..C5)"
@@ -279,6 +285,53 @@ def measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, pla
     }
 
     return swap
+
+
+def recompute_bench(torch, mb, args):
+    """Token-wise recomputation (Section 4.1) of one GPU's share of a 7B layer: input_norm =
+    LayerNorm(x) over h = 4096 and q,k,v = input_norm . W^T (N = 1536) on the dropped rows [k,S).
+    LayerNorm is HBM-bound (reads and writes h bf16 per row), the projection MFMA-bound
+    (2*K*N flop per row); both are timed with events on the launch stream."""
+    S, h, N, eps = int(args.recompute), 4096, 1536, 1e-5
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    x = torch.randn((S, h), generator=gen, device="cuda").to(torch.bfloat16)
+    gamma = torch.ones(h, dtype=torch.bfloat16, device="cuda")
+    beta = torch.zeros(h, dtype=torch.bfloat16, device="cuda")
+    w = (torch.randn((N, h), generator=gen, device="cuda") / h ** 0.5).to(torch.bfloat16)
+    bias = torch.zeros(N, dtype=torch.bfloat16, device="cuda")
+    norm = torch.empty_like(x)
+    qkv = torch.empty((S, N), dtype=torch.bfloat16, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    rows_out = []
+    for alpha in [float(a) for a in args.alphas.split(",")]:
+        k = mb.memo_split_tokens(S, alpha)
+        n = S - k
+        t_ln = t_lin = 0.0
+        reps = max(1, args.steps)
+        for r in range(args.warmup + reps):
+            e = [ev() for _ in range(3)]
+            e[0].record()
+            mb.memo_layernorm_rows(x, gamma, beta, eps, y=norm, rows=(k, S))
+            e[1].record()
+            mb.memo_linear_rows(norm, w, bias, out=qkv, rows=(k, S))
+            e[2].record()
+            torch.cuda.synchronize()
+            if r >= args.warmup:
+                t_ln += e[0].elapsed_time(e[1]) / reps
+                t_lin += e[1].elapsed_time(e[2]) / reps
+        ln_bytes, lin_flop = 2.0 * n * h * 2, 2.0 * n * h * N
+        rows_out.append({"alpha": alpha, "rows_recomputed": n, "layernorm_ms": t_ln, "linear_ms": t_lin,
+                         "layernorm_GBps": ln_bytes / (t_ln * 1e-3) / 1e9 if n else None,
+                         "linear_TFLOPs": lin_flop / (t_lin * 1e-3) / 1e12 if n else None})
+    full = rows_out[0] if rows_out and rows_out[0]["rows_recomputed"] == S else None
+    out = {"metric": "token-wise recomputation of input_norm and q,k,v", "unit": "ms", "S": S, "h": h, "N": N,
+           "rows": rows_out,
+           "roofline_layernorm": None if not full else {"bound": "hbm", "achieved": full["layernorm_GBps"], "peak": 8000.0,
+                                                        "unit": "GB/s", "frac": full["layernorm_GBps"] / 8000.0},
+           "roofline_linear": None if not full else {"bound": "mfma", "achieved": full["linear_TFLOPs"],
+                                                     "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                                     "frac": full["linear_TFLOPs"] / BF16_MFMA_PEAK_TFLOPS}}
+    print(json.dumps(out), flush=True)
 
 
 def schedule_bench(torch, mb, synth, args):

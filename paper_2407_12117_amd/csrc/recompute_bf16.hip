@@ -14,6 +14,7 @@ namespace {
 // passes over the registers (mean, then centred sum of squares).  HBM-bound: 2*h*2 bytes per row.
 constexpr int kLnMaxChunks = 16;            // h <= 8192
 
+template <int NCH>                          // h = 512 * NCH: the row lives in 8 * NCH registers per lane
 __global__ __launch_bounds__(256) void layernorm_rows_bf16_kernel(const __bf16 *x, const __bf16 *gamma,
                                                                   const __bf16 *beta, __bf16 *y, int64_t row_begin,
                                                                   int64_t row_end, int h, float eps)
@@ -21,12 +22,12 @@ __global__ __launch_bounds__(256) void layernorm_rows_bf16_kernel(const __bf16 *
     const int lane = threadIdx.x & 63;
     const int64_t row = row_begin + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= row_end) return;
-    const int nch = h / 512;
+    constexpr int nch = NCH;
     const __bf16 *xr = x + row * h;
-    float v[kLnMaxChunks][8];
+    float v[NCH][8];
     float sum = 0.f;
 #pragma unroll
-    for (int c = 0; c < kLnMaxChunks; ++c) {
+    for (int c = 0; c < NCH; ++c) {
         if (c < nch) {
             const bf16x8 raw = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(xr + c * 512 + lane * 8));
 #pragma unroll
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(256) void layernorm_rows_bf16_kernel(const __bf16 *
     const float mean = sum / (float)h;
     float sq = 0.f;
 #pragma unroll
-    for (int c = 0; c < kLnMaxChunks; ++c)
+    for (int c = 0; c < NCH; ++c)
         if (c < nch)
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(256) void layernorm_rows_bf16_kernel(const __bf16 *
     const float rstd = 1.0f / sqrtf(sq / (float)h + eps);
     __bf16 *yr = y + row * h;
 #pragma unroll
-    for (int c = 0; c < kLnMaxChunks; ++c) {
+    for (int c = 0; c < NCH; ++c) {
         if (c < nch) {
             const bf16x8 gm = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(gamma + c * 512 + lane * 8));
             const bf16x8 bt = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(beta + c * 512 + lane * 8));
@@ -73,94 +74,117 @@ __global__ __launch_bounds__(256) void layernorm_rows_bf16_kernel(const __bf16 *
 
 // ---------------------------------------------------------------------------- projection
 // out[token, feature] = sum_c a[token, c] * w[feature, c] + bias[feature]   (w as [N, K], K contiguous)
-// Workgroup: 8 waves, 128 tokens x 128 features; K streamed in chunks of 128 through a
-// double-buffered LDS ring of swizzled 64-row tiles (2 token tiles + 2 weight tiles per stage).
-// Wave w owns tokens 32*(w%4).. and features 64*(w/4)..: D[feature, token] = W_rows * A_rows^T,
-// so a lane holds one token and 4 consecutive features per register group (8-byte stores).
-struct TripleSlot { bf16x8 b, a0, a1; };
+// Workgroup: 8 waves, 256 tokens x 256 features; K streamed in chunks of 64 through a double-buffered
+// LDS ring (32 KB of token rows + 32 KB of weight rows per stage).  The fills are what bounds this
+// kernel (bytes into LDS per MFMA), hence the large tile.  Wave w owns tokens 64*(w%4).. (2 blocks)
+// and features 128*(w/4).. (4 blocks): D[feature, token] = W_rows * A_rows^T, so a lane holds one
+// token and 4 consecutive features per register group (8-byte stores); per 16-wide k-step a wave
+// reads 2 + 4 operands for 8 MFMAs.
+//
+// LDS rows here are 128 bytes (64 bf16): chunk c (16 bytes) of row r sits at position
+// c ^ ((r >> 1) & 7), which keeps 16 lanes reading one chunk column of 16 consecutive rows on
+// distinct banks.  One global_load_lds_dwordx4 moves 8 rows.
+struct SixSlot { bf16x8 b[2], a[4]; };
 
 template <int N>
-__device__ __forceinline__ void lds_wait(TripleSlot &x)
+__device__ __forceinline__ void lds_wait(SixSlot &x)
 {
     static_assert(N >= 0 && N <= 15, "lgkmcnt range");
-    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(x.b), "+v"(x.a0), "+v"(x.a1) : "n"(N));
+    asm volatile("s_waitcnt lgkmcnt(%6)"
+                 : "+v"(x.b[0]), "+v"(x.b[1]), "+v"(x.a[0]), "+v"(x.a[1]), "+v"(x.a[2]), "+v"(x.a[3])
+                 : "n"(N));
 }
 
-constexpr int kLinBm = 128, kLinBn = 128, kLinBk = 128;
+constexpr int kLinBm = 256, kLinBn = 256, kLinBk = 64;
+constexpr int kLinTile = 256 * 128;          // bytes of one operand's stage
 
 __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *a, const __bf16 *w, const __bf16 *bias,
                                                                   __bf16 *out, int64_t row_begin, int64_t row_end,
                                                                   int K, int N)
 {
-    // token tiles [buf][2] in the first 64 KB, weight tiles [buf][2] in the second: each operand's
-    // two buffers lie within the 64 KB an LDS immediate offset can reach from one address register
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[8 * kTileBytes];
+    // token rows [buf] in the first 64 KB, weight rows [buf] in the second: each operand's two buffers
+    // lie within the 64 KB an LDS immediate offset can reach from one address register
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kLinTile];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tb = wave & 3, fh = wave >> 2;
-    const int ntn = N / kLinBn;
+    const int ntn = (N + kLinBn - 1) / kLinBn;
     const int64_t mt = blockIdx.x / ntn;              // consecutive workgroups share the token rows
     const int nt = (int)(blockIdx.x % ntn);
     const int64_t m0 = row_begin + mt * kLinBm;
     const int n0 = nt * kLinBn;
-    const LaneAddr la = make_lane_addr(lane);
-    const LdsAddr ad = make_lds_addr(lds, la);
-    uint32_t tok_addr[8], wgt_addr[8];
+
+    // operand read addresses: row l32 of a 32-row block, chunk 2*kc + half, kc = 0..3
+    uint32_t tok_addr[4], wgt_addr[4];
 #pragma unroll
-    for (int kc = 0; kc < 8; ++kc) {
-        tok_addr[kc] = ad.row[kc] + (uint32_t)(tb * 8192);
-        wgt_addr[kc] = ad.row[kc] + (uint32_t)(4 * kTileBytes + fh * 16384);
+    for (int kc = 0; kc < 4; ++kc) {
+        const uint32_t in_block = (uint32_t)(l32 * 128 + ((((2 * kc + half) ^ ((l32 >> 1) & 7))) << 4));
+        tok_addr[kc] = (uint32_t)(uintptr_t)lds + in_block + (uint32_t)(tb * 64 * 128);
+        wgt_addr[kc] = (uint32_t)(uintptr_t)lds + in_block + (uint32_t)(2 * kLinTile + fh * 128 * 128);
     }
-    const TileOffsets<8> toff = make_tile_offsets<8>(K, wave, lane);
-    const bool full_rows = m0 + kLinBm <= row_end;
+    // fills: instruction n of this wave covers stage rows 8*(4*wave + n) + lane/8, position lane%8
+    const bool full_tok = m0 + kLinBm <= row_end, full_wgt = n0 + kLinBn <= N;
+    uint32_t tok_off[4], wgt_off[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int row = 8 * (4 * wave + n) + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        int64_t tr = m0 + row, wr = n0 + row;
+        tr = tr < row_end ? tr : row_end - 1;         // rows past the range repeat the last one, never stored
+        wr = wr < N ? wr : N - 1;
+        tok_off[n] = (uint32_t)((tr - m0) * K * 2 + chunk * 16);
+        wgt_off[n] = (uint32_t)((wr - n0) * K * 2 + chunk * 16);
+    }
+    (void)full_tok; (void)full_wgt;
+    const char *abase = reinterpret_cast<const char *>(a + m0 * K);
+    const char *wbase = reinterpret_cast<const char *>(w + (int64_t)n0 * K);
     const int nchunks = K / kLinBk;
 
-    // queue the fill of K-chunk c into ring buffer `buf`
     auto fill_chunk = [&](int buf, int c) {
-        LDS_AS unsigned char *tdst = lds + buf * 2 * kTileBytes, *wdst = lds + (4 + buf * 2) * kTileBytes;
-        const char *wbase = reinterpret_cast<const char *>(w + (int64_t)n0 * K + (int64_t)c * kLinBk);
+        LDS_AS unsigned char *tdst = lds + buf * kLinTile + (4 * wave) * 1024;
+        LDS_AS unsigned char *wdst = lds + (2 + buf) * kLinTile + (4 * wave) * 1024;
+        const char *ab = abase + (int64_t)c * kLinBk * 2, *wb = wbase + (int64_t)c * kLinBk * 2;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            if (full_rows) {
-                const char *abase = reinterpret_cast<const char *>(a + (m0 + 64 * t) * K + (int64_t)c * kLinBk);
-                fill_full_tile_part(tdst + t * kTileBytes, toff, 0, abase, wave);
-                fill_full_tile_part(tdst + t * kTileBytes, toff, 1, abase, wave);
-            } else {
-                // rows past row_end re-read row row_end-1 (finite values, never stored)
-                fill_ragged_tile<8>(tdst + t * kTileBytes, a + (int64_t)c * kLinBk, K, m0 + 64 * t, row_end, wave, lane);
-            }
-            const char *wt = wbase + (int64_t)(64 * t) * K * 2;
-            fill_full_tile_part(wdst + t * kTileBytes, toff, 0, wt, wave);
-            fill_full_tile_part(wdst + t * kTileBytes, toff, 1, wt, wave);
+        for (int n = 0; n < 4; ++n) {
+            __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ab + tok_off[n]), (LDS_AS void *)(tdst + n * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const GLB_AS void *)(wb + wgt_off[n]), (LDS_AS void *)(wdst + n * 1024), 16, 0, 0);
         }
     };
 
-    f32x16 acc[2];
+    f32x16 acc[4][2];                                 // [feature block][token block]
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[cb][e] = 0.f;
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[cb][t][e] = 0.f;
 
     fill_chunk(0, 0);
     auto stage = [&](auto bufc, int c) {
         constexpr int BUF = decltype(bufc)::value;
-        constexpr int off = BUF * 2 * kTileBytes;
+        constexpr int off = BUF * kLinTile;
         wait_fills();
         __syncthreads();          // chunk c is complete; nobody still reads the other buffer
         if (c + 1 < nchunks) fill_chunk(BUF ^ 1, c + 1);
-        TripleSlot ring[3];
-        auto issue = [&](auto n, TripleSlot &slot) {
+        SixSlot ring[2];
+        auto issue = [&](auto n, SixSlot &slot) {
             constexpr int kc = decltype(n)::value;
-            lds_issue_b128<off>(slot.b, tok_addr[kc]);
-            lds_issue_b128<off>(slot.a0, wgt_addr[kc]);
-            lds_issue_b128<off + 8192>(slot.a1, wgt_addr[kc]);
+            lds_issue_b128<off>(slot.b[0], tok_addr[kc]);
+            lds_issue_b128<off + 32 * 128>(slot.b[1], tok_addr[kc]);
+            lds_issue_b128<off>(slot.a[0], wgt_addr[kc]);
+            lds_issue_b128<off + 32 * 128>(slot.a[1], wgt_addr[kc]);
+            lds_issue_b128<off + 64 * 128>(slot.a[2], wgt_addr[kc]);
+            lds_issue_b128<off + 96 * 128>(slot.a[3], wgt_addr[kc]);
         };
-        lds_pipeline_prologue<8, 2, 3>(ring, issue);
-        lds_pipeline_body<8, 2, 3>(ring, issue, [&](auto n, TripleSlot &slot) {
-            acc[0] = mfma32(slot.a0, slot.b, acc[0]);
-            acc[1] = mfma32(slot.a1, slot.b, acc[1]);
+        lds_pipeline_prologue<4, 1, 6>(ring, issue);
+        lds_pipeline_body<4, 1, 6>(ring, issue, [&](auto n, SixSlot &slot) {
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) {
+                acc[cb][0] = mfma32(slot.a[cb], slot.b[0], acc[cb][0]);
+                acc[cb][1] = mfma32(slot.a[cb], slot.b[1], acc[cb][1]);
+            }
         });
     };
     for (int c = 0; c < nchunks; c += 2) {
@@ -168,31 +192,35 @@ __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *
         if (c + 1 < nchunks) stage(IntC<1>{}, c + 1);
     }
 
-    // acc[cb][4g + r] = out[token m0 + 32 tb + l32][feature n0 + 64 fh + 32 cb + 8 g + 4 half + r]
-    const int64_t token = m0 + 32 * tb + l32;
-    if (token < row_end) {
-        __bf16 *orow = out + token * N + n0 + 64 * fh + 4 * half;
-        const __bf16 *brow = bias ? bias + n0 + 64 * fh + 4 * half : nullptr;
+    // acc[cb][t][4g + r] = out[token m0 + 64 tb + 32 t + l32][feature n0 + 128 fh + 32 cb + 8 g + 4 half + r]
+    if (n0 + 128 * fh < N) {                          // N is a multiple of 128: a feature half is whole or absent
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int t = 0; t < 2; ++t) {
+            const int64_t token = m0 + 64 * tb + 32 * t + l32;
+            if (token >= row_end) continue;
+            __bf16 *orow = out + token * N + n0 + 128 * fh + 4 * half;
+            const __bf16 *brow = bias ? bias + n0 + 128 * fh + 4 * half : nullptr;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float b4[4] = {0.f, 0.f, 0.f, 0.f};
-                if (brow) {
-                    const u32x2 braw = *reinterpret_cast<const u32x2 *>(brow + 32 * cb + 8 * g);
-                    // elements copied to scalars first: a bit cast applied to a vector element
-                    // directly reads element 0 for both with this compiler
-                    const uint32_t r0 = braw[0], r1 = braw[1];
-                    const bf16x2 lo = __builtin_bit_cast(bf16x2, r0), hi = __builtin_bit_cast(bf16x2, r1);
-                    b4[0] = (float)lo[0]; b4[1] = (float)lo[1]; b4[2] = (float)hi[0]; b4[3] = (float)hi[1];
+            for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float b4[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (brow) {
+                        const u32x2 braw = *reinterpret_cast<const u32x2 *>(brow + 32 * cb + 8 * g);
+                        // elements copied to scalars first: a bit cast applied to a vector element
+                        // directly reads element 0 for both with this compiler
+                        const uint32_t r0 = braw[0], r1 = braw[1];
+                        const bf16x2 lo = __builtin_bit_cast(bf16x2, r0), hi = __builtin_bit_cast(bf16x2, r1);
+                        b4[0] = (float)lo[0]; b4[1] = (float)lo[1]; b4[2] = (float)hi[0]; b4[3] = (float)hi[1];
+                    }
+                    f32x2 p = {acc[cb][t][4 * g] + b4[0], acc[cb][t][4 * g + 1] + b4[1]};
+                    f32x2 q = {acc[cb][t][4 * g + 2] + b4[2], acc[cb][t][4 * g + 3] + b4[3]};
+                    u32x2 wv;
+                    wv[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+                    wv[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(q, bf16x2));
+                    *reinterpret_cast<u32x2 *>(orow + 32 * cb + 8 * g) = wv;
                 }
-                f32x2 p = {acc[cb][4 * g] + b4[0], acc[cb][4 * g + 1] + b4[1]};
-                f32x2 q = {acc[cb][4 * g + 2] + b4[2], acc[cb][4 * g + 3] + b4[3]};
-                u32x2 wv;
-                wv[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
-                wv[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(q, bf16x2));
-                *reinterpret_cast<u32x2 *>(orow + 32 * cb + 8 * g) = wv;
-            }
+        }
     }
 }
 
@@ -204,10 +232,20 @@ hipError_t launch_layernorm_rows_bf16(const void *x, const void *gamma, const vo
     const int64_t rows = row_end - row_begin;
     if (rows <= 0) return hipSuccess;
     const int64_t blocks = (rows + 3) / 4;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    layernorm_rows_bf16_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>(
-        static_cast<const __bf16 *>(x), static_cast<const __bf16 *>(gamma), static_cast<const __bf16 *>(beta),
-        static_cast<__bf16 *>(y), row_begin, row_end, h, eps);
+    if (blocks > 0x7fffffffLL || h % 512 || h / 512 > kLnMaxChunks) return hipErrorInvalidValue;
+    const __bf16 *xp = static_cast<const __bf16 *>(x), *gp = static_cast<const __bf16 *>(gamma);
+    const __bf16 *bp = static_cast<const __bf16 *>(beta);
+    __bf16 *yp = static_cast<__bf16 *>(y);
+    const dim3 grid((unsigned)blocks);
+    switch (h / 512) {
+#define MEMO_LN_CASE(n) \
+    case n: layernorm_rows_bf16_kernel<n><<<grid, 256, 0, st>>>(xp, gp, bp, yp, row_begin, row_end, h, eps); break;
+        MEMO_LN_CASE(1) MEMO_LN_CASE(2) MEMO_LN_CASE(3) MEMO_LN_CASE(4) MEMO_LN_CASE(5) MEMO_LN_CASE(6)
+        MEMO_LN_CASE(7) MEMO_LN_CASE(8) MEMO_LN_CASE(9) MEMO_LN_CASE(10) MEMO_LN_CASE(11) MEMO_LN_CASE(12)
+        MEMO_LN_CASE(13) MEMO_LN_CASE(14) MEMO_LN_CASE(15) MEMO_LN_CASE(16)
+#undef MEMO_LN_CASE
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
@@ -216,7 +254,9 @@ hipError_t launch_linear_rows_bf16(const void *a, const void *w, const void *bia
 {
     const int64_t rows = row_end - row_begin;
     if (rows <= 0) return hipSuccess;
-    const int64_t blocks = ((rows + kLinBm - 1) / kLinBm) * (N / kLinBn);
+    const int64_t blocks = ((rows + kLinBm - 1) / kLinBm) * ((N + kLinBn - 1) / kLinBn);
+    // 256 rows of either operand must span < 4 GiB (32-bit per-lane offsets)
+    if ((int64_t)kLinBm * K * 2 >= (1LL << 32)) return hipErrorInvalidValue;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     linear_rows_bf16_kernel<<<dim3((unsigned)blocks), 512, 0, st>>>(
         static_cast<const __bf16 *>(a), static_cast<const __bf16 *>(w), static_cast<const __bf16 *>(bias),
