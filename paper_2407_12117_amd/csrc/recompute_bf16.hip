@@ -111,8 +111,15 @@ __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tb = wave & 3, fh = wave >> 2;
     const int ntn = (N + kLinBn - 1) / kLinBn;
-    const int64_t mt = blockIdx.x / ntn;              // consecutive workgroups share the token rows
-    const int nt = (int)(blockIdx.x % ntn);
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  The ids are remapped so
+    // that every XCD works through a contiguous range of (token tile, feature tile) pairs with the
+    // feature tile running fastest: the workgroups that share a token tile then run on one XCD close
+    // in time, and the token rows are fetched from HBM once instead of once per feature tile.
+    const int64_t nblk = gridDim.x, per = nblk / 8, rem = nblk % 8;
+    const int64_t xcd = blockIdx.x % 8, idx = blockIdx.x / 8;
+    const int64_t logical = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    const int64_t mt = logical / ntn;
+    const int nt = (int)(logical % ntn);
     const int64_t m0 = row_begin + mt * kLinBm;
     const int n0 = nt * kLinBn;
 
