@@ -346,23 +346,30 @@ def schedule_bench(torch, mb, synth, args):
     scale = synth.default_scale(d)
     alphas = [float(a) for a in args.alphas.split(",")]
     rows = []
+    # One set of streams for every stack: HIP maps streams onto 4 hardware queues, and a stack whose
+    # copy stream shares a queue with its compute stream would not overlap anything.
+    streams = tuple(torch.cuda.Stream() for _ in range(3))
 
     def run(stack, x0, g, iters):
-        stack.forward(x0); stack.backward(g)               # warm-up iteration
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(iters):
+        """Median wall time of one iteration (forward + backward, synchronised at its ends)."""
+        times = []
+        for i in range(iters + 1):                         # the first iteration is a warm-up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
             stack.forward(x0)
             stack.backward(g)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / iters
+            torch.cuda.synchronize()
+            if i > 0:
+                times.append(time.perf_counter() - t0)
+        times.sort()
+        return times[len(times) // 2]
 
     for S in [int(x) for x in args.schedule.split(",")]:
         gen = torch.Generator(device="cuda").manual_seed(4242)
         x0 = torch.randn((S, H * d), generator=gen, device="cuda").to(torch.bfloat16)
         g = torch.randn((S, H * d), generator=gen, device="cuda").to(torch.bfloat16)
-        iters = max(1, args.steps)
-        res = ls.LayerStack(n, S, H, d, 1.0, scale, swap=False)
+        iters = max(3, args.steps)
+        res = ls.LayerStack(n, S, H, d, 1.0, scale, swap=False, streams=streams)
         t_res = run(res, x0, g, iters)
         torch.cuda.synchronize()
         t0 = time.perf_counter(); res.forward(x0); torch.cuda.synchronize()
@@ -374,7 +381,10 @@ def schedule_bench(torch, mb, synth, args):
         _, _, layer_host = mb.memo_buffer_plan_make(S, ls.layer_tensors(H, d, 1.0))
         host = torch.empty(max(n - 2, 1) * layer_host, dtype=torch.uint8, pin_memory=True)
         probe = torch.empty(layer_host, dtype=torch.uint8, device="cuda")
-        side = torch.cuda.Stream()
+        for i in range(max(n - 2, 1)):                     # first touch of every pinned page, untimed
+            host[i * layer_host:(i + 1) * layer_host].copy_(probe, non_blocking=True)
+        torch.cuda.synchronize()
+        side = streams[1]
         rate = {}
         for name, fn in (("d2h", mb.memo_swap_out), ("h2d", mb.memo_swap_in)):
             fn(probe.view(S, -1), 1.0, host, side); torch.cuda.synchronize()
@@ -387,7 +397,7 @@ def schedule_bench(torch, mb, synth, args):
         except mb.MemoError:
             a_star = None
         for alpha in alphas + ([round(a_star, 3)] if a_star is not None and a_star < 1.0 else []):
-            st = ls.LayerStack(n, S, H, d, alpha, scale, swap=True, host=host)
+            st = ls.LayerStack(n, S, H, d, alpha, scale, swap=True, host=host, streams=streams)
             t_swap = run(st, x0, g, iters)
             hb = st.host_bytes
             st.close(); del st

@@ -57,17 +57,20 @@ class LayerStack:
     buffers (swap=False; the reference the swapped run must reproduce bit for bit)."""
 
     def __init__(self, n_layers, S, H, d, alpha, scale, swap=True, n_saved=N_SAVED,
-                 device="cuda:0", host=None):
-        """host: optional pinned uint8 tensor to use as the host store (allocated if None)."""
+                 device="cuda:0", host=None, streams=None):
+        """host: optional pinned uint8 tensor to use as the host store (allocated if None).
+        streams: optional (compute, offload, prefetch) to reuse.  HIP multiplexes streams onto a
+        few hardware queues (4 by default); two of the three landing on one queue would serialise
+        copies and compute, so a caller that builds many stacks should create the streams once."""
         if d != 128:
             raise ValueError("the bf16 attention path needs d = 128")
         self.n, self.S, self.H, self.d, self.scale, self.swap = n_layers, S, H, d, scale, swap
         self.tensors = layer_tensors(H, d, alpha, n_saved)
         self.slots, self.dev_bytes, self.host_bytes = mb.memo_buffer_plan_make(S, self.tensors)
         dev = torch.device(device)
-        self.compute = torch.cuda.Stream(device=dev)
-        self.offload = torch.cuda.Stream(device=dev)
-        self.prefetch = torch.cuda.Stream(device=dev)
+        if streams is None:
+            streams = tuple(torch.cuda.Stream(device=dev) for _ in range(3))
+        self.compute, self.offload, self.prefetch = streams
         n_buf = 2 if swap else n_layers
         self.buffers = [torch.empty(self.dev_bytes, dtype=torch.uint8, device=dev)
                         for _ in range(n_buf)]
