@@ -50,7 +50,7 @@ typedef enum { MEMO_F32 = 0, MEMO_BF16 = 1 } memo_dtype;
  *            MEMO_F32 with d in {64, 128} (fp32 throughout).
  * S may be any positive length (ragged last tile is handled); causal must be 1.
  * Rows must be 16-byte aligned: base pointers 16-byte aligned and strides a
- * multiple of 8 (bf16) or 4 (fp32) elements.
+ * multiple of 8 (bf16) or 4 (fp32) elements.  MEMO_BF16: stride_s <= 2^24 elements.
  */
 typedef struct {
     int32_t B, H, d;

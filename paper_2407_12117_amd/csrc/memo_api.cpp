@@ -27,6 +27,8 @@ memo_status check_desc(const memo_attn_desc *d, memo::AttnArgs *out)
     if (d->stride_b % vec || d->stride_s % vec || d->stride_h % vec) return MEMO_ERR_UNSUPPORTED;
     // the tile index arithmetic is 64-bit; the row count per launch must fit the grid
     if (d->S > ((int64_t)1 << 31) - 1024) return MEMO_ERR_UNSUPPORTED;
+    // the bf16 tile fills address 64 rows with 32-bit per-lane byte offsets
+    if (d->dtype == MEMO_BF16 && d->stride_s > ((int64_t)1 << 24)) return MEMO_ERR_UNSUPPORTED;
     std::memset(out, 0, sizeof(*out));
     out->B = d->B;
     out->H = d->H;

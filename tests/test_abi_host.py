@@ -82,6 +82,7 @@ def _desc(**kw):
     (dict(dtype=7), mb.MEMO_ERR_UNSUPPORTED),
     (dict(stride_s=132), mb.MEMO_ERR_UNSUPPORTED),    # rows not 16-byte aligned
     (dict(stride_s=64), mb.MEMO_ERR_INVALID_ARG),     # rows overlap
+    (dict(stride_s=(1 << 24) + 8, stride_b=1 << 40), mb.MEMO_ERR_UNSUPPORTED),   # 64 rows span over 4 GiB
 ])
 def test_attention_rejects_bad_descriptors_before_any_launch(kw, status):
     d = _desc(**kw)
