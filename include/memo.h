@@ -248,6 +248,57 @@ memo_status memo_linear_rows(const void *a, const void *w, const void *bias, voi
                              int32_t K, int32_t N, int64_t row_begin, int64_t row_end,
                              void *hip_stream);
 
+/*
+ * Offline storage allocation for the transient tensors and its two-level use over identical
+ * layers (Section 4.2).  Host-side arithmetic only; nothing touches a GPU.
+ *
+ * A request is a tensor of `size` bytes alive during the ticks [start, end) of a profiled
+ * memory request sequence.  memo_dsa_plan assigns every request an address such that requests
+ * with overlapping lifespans do not share bytes and the peak  max(addr + size)  is minimal:
+ * the optimum of the paper's mixed-integer programme, found by an exact search that is cut
+ * off after `node_limit` search nodes (then the best plan found so far is returned and
+ * *optimal_out is 0; it is 1 when the plan is proven optimal).  Sizes are rounded up to
+ * `align` (a power of two) first; addresses are multiples of it.  addr_out has n entries.
+ *
+ * memo_trace_to_requests turns a sequence of "malloc tensor_id size" / "free tensor_id size"
+ * events (is_malloc[t] != 0 for a malloc) into requests in order of allocation: start = index
+ * of the malloc, end = index of the free (the sequence length if never freed).  req_out and
+ * id_out need room for one entry per malloc.  A double malloc, a free without a live
+ * allocation or with another size give MEMO_ERR_INVALID_ARG.
+ *
+ * memo_dsa_plan_bilevel: level 1 plans one layer's forward and one layer's backward request
+ * sequence (every layer reuses the offsets); level 2 plans the rest of the model (`outer`)
+ * together with one pseudo request per layer pass, of the level-1 peak, alive during the tick
+ * [fwd_ticks[l], fwd_ticks[l] + 1) resp. [bwd_ticks[l], bwd_ticks[l] + 1) of the outer clock.
+ * The address of tensor t of layer l's forward pass is fwd_base[l] + fwd_offsets[t].
+ * The caller provides the arrays of memo_bilevel_plan (n_fwd, n_bwd, n_layers, n_layers,
+ * n_outer entries); peaks and `optimal` are filled in.
+ */
+typedef struct {
+    int64_t size;
+    int32_t start, end;
+} memo_dsa_request;
+
+typedef struct {
+    int64_t peak;               /* bytes needed for all transient tensors of the model */
+    int64_t fwd_peak, bwd_peak; /* level 1: bytes of one layer's forward / backward pass */
+    int64_t *fwd_offsets, *bwd_offsets, *fwd_base, *bwd_base, *outer_addr;
+    int32_t optimal;            /* 1 if all three searches proved their optimum */
+} memo_bilevel_plan;
+
+memo_status memo_trace_to_requests(int32_t n_events, const int32_t *is_malloc,
+                                   const int64_t *tensor_id, const int64_t *size,
+                                   memo_dsa_request *req_out, int64_t *id_out,
+                                   int32_t *n_requests_out);
+memo_status memo_dsa_plan(int32_t n, const memo_dsa_request *requests, int64_t align,
+                          int64_t node_limit, int64_t *addr_out, int64_t *peak_out,
+                          int32_t *optimal_out);
+memo_status memo_dsa_plan_bilevel(int32_t n_fwd, const memo_dsa_request *layer_fwd, int32_t n_bwd,
+                                  const memo_dsa_request *layer_bwd, int32_t n_layers,
+                                  const int32_t *fwd_ticks, const int32_t *bwd_ticks,
+                                  int32_t n_outer, const memo_dsa_request *outer, int64_t align,
+                                  int64_t node_limit, memo_bilevel_plan *out);
+
 /* Pinned host memory helpers (hipHostMalloc / hipHostFree). */
 memo_status memo_host_alloc(void **host_ptr, size_t bytes);
 memo_status memo_host_free(void *host_ptr);

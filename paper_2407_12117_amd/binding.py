@@ -30,6 +30,7 @@ EXPORTS = [
     "memo_sched_forward_end", "memo_sched_backward_begin", "memo_sched_backward_end",
     "memo_sched_buffer", "memo_sched_destroy",
     "memo_layernorm_rows", "memo_linear_rows",
+    "memo_trace_to_requests", "memo_dsa_plan", "memo_dsa_plan_bilevel",
 ]
 
 
@@ -55,6 +56,17 @@ class MemoTensorDesc(ctypes.Structure):
 class MemoTensorSlot(ctypes.Structure):
     _fields_ = [("dev_offset", ctypes.c_int64), ("host_offset", ctypes.c_int64),
                 ("k_swapped", ctypes.c_int64), ("bytes_swapped", ctypes.c_size_t)]
+
+
+class MemoDsaRequest(ctypes.Structure):
+    _fields_ = [("size", ctypes.c_int64), ("start", ctypes.c_int32), ("end", ctypes.c_int32)]
+
+
+class MemoBilevelPlan(ctypes.Structure):
+    _fields_ = [("peak", ctypes.c_int64), ("fwd_peak", ctypes.c_int64), ("bwd_peak", ctypes.c_int64),
+                ("fwd_offsets", ctypes.POINTER(ctypes.c_int64)), ("bwd_offsets", ctypes.POINTER(ctypes.c_int64)),
+                ("fwd_base", ctypes.POINTER(ctypes.c_int64)), ("bwd_base", ctypes.POINTER(ctypes.c_int64)),
+                ("outer_addr", ctypes.POINTER(ctypes.c_int64)), ("optimal", ctypes.c_int32)]
 
 
 class MemoError(RuntimeError):
@@ -118,6 +130,14 @@ def lib():
     L.memo_sched_buffer.restype = vp
     L.memo_sched_destroy.argtypes = [vp]
     L.memo_sched_destroy.restype = ctypes.c_int
+    rp, i64p, i32p = ctypes.POINTER(MemoDsaRequest), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int32)
+    L.memo_trace_to_requests.argtypes = [ctypes.c_int32, i32p, i64p, i64p, rp, i64p, i32p]
+    L.memo_trace_to_requests.restype = ctypes.c_int
+    L.memo_dsa_plan.argtypes = [ctypes.c_int32, rp, i64, i64, i64p, i64p, i32p]
+    L.memo_dsa_plan.restype = ctypes.c_int
+    L.memo_dsa_plan_bilevel.argtypes = [ctypes.c_int32, rp, ctypes.c_int32, rp, ctypes.c_int32, i32p, i32p,
+                                        ctypes.c_int32, rp, i64, i64, ctypes.POINTER(MemoBilevelPlan)]
+    L.memo_dsa_plan_bilevel.restype = ctypes.c_int
     L.memo_layernorm_rows.argtypes = [vp, vp, vp, vp, i64, ctypes.c_int32, ctypes.c_float, i64, i64, vp]
     L.memo_layernorm_rows.restype = ctypes.c_int
     L.memo_linear_rows.argtypes = [vp, vp, vp, vp, i64, ctypes.c_int32, ctypes.c_int32, i64, i64, vp]
@@ -413,4 +433,58 @@ def memo_linear_rows(a, w, bias=None, out=None, rows=None, stream=None):
     b, e = _row_range(rows, S)
     _check(lib().memo_linear_rows(a.data_ptr(), w.data_ptr(), None if bias is None else bias.data_ptr(),
                                   out.data_ptr(), S, K, N, b, e, _stream_ptr(stream)), "memo_linear_rows")
+    return out
+
+
+def _requests(reqs):
+    arr = (MemoDsaRequest * max(len(reqs), 1))()
+    for i, (size, start, end) in enumerate(reqs):
+        arr[i].size, arr[i].start, arr[i].end = int(size), int(start), int(end)
+    return arr
+
+
+def memo_trace_to_requests(events):
+    """events: list of ("malloc" | "free", tensor_id (int), size).  Returns (requests, ids)."""
+    n = len(events)
+    flags = (ctypes.c_int32 * max(n, 1))(*[1 if e[0] == "malloc" else 0 for e in events])
+    ids = (ctypes.c_int64 * max(n, 1))(*[int(e[1]) for e in events])
+    sizes = (ctypes.c_int64 * max(n, 1))(*[int(e[2]) for e in events])
+    req = (MemoDsaRequest * max(n, 1))()
+    out_ids = (ctypes.c_int64 * max(n, 1))()
+    cnt = ctypes.c_int32(0)
+    _check(lib().memo_trace_to_requests(n, flags, ids, sizes, req, out_ids, ctypes.byref(cnt)),
+           "memo_trace_to_requests")
+    k = cnt.value
+    return [(req[i].size, req[i].start, req[i].end) for i in range(k)], [out_ids[i] for i in range(k)]
+
+
+def memo_dsa_plan(requests, align=1, node_limit=1_000_000):
+    """requests: list of (size, start, end).  Returns (peak, addresses, proven_optimal)."""
+    n = len(requests)
+    addr = (ctypes.c_int64 * max(n, 1))()
+    peak, opt = ctypes.c_int64(0), ctypes.c_int32(0)
+    _check(lib().memo_dsa_plan(n, _requests(requests), int(align), int(node_limit), addr,
+                               ctypes.byref(peak), ctypes.byref(opt)), "memo_dsa_plan")
+    return peak.value, [addr[i] for i in range(n)], bool(opt.value)
+
+
+def memo_dsa_plan_bilevel(layer_fwd, layer_bwd, fwd_ticks, bwd_ticks, outer, align=1, node_limit=1_000_000):
+    """Two-level plan; returns a dict like the oracle's."""
+    nl = len(fwd_ticks)
+    if len(bwd_ticks) != nl:
+        raise ValueError("fwd_ticks and bwd_ticks must have one entry per layer")
+    arrs = {name: (ctypes.c_int64 * max(k, 1))() for name, k in
+            (("fwd_offsets", len(layer_fwd)), ("bwd_offsets", len(layer_bwd)), ("fwd_base", nl),
+             ("bwd_base", nl), ("outer_addr", len(outer)))}
+    plan = MemoBilevelPlan()
+    for name, arr in arrs.items():
+        setattr(plan, name, ctypes.cast(arr, ctypes.POINTER(ctypes.c_int64)))
+    ft = (ctypes.c_int32 * max(nl, 1))(*[int(t) for t in fwd_ticks])
+    bt = (ctypes.c_int32 * max(nl, 1))(*[int(t) for t in bwd_ticks])
+    _check(lib().memo_dsa_plan_bilevel(len(layer_fwd), _requests(layer_fwd), len(layer_bwd), _requests(layer_bwd),
+                                       nl, ft, bt, len(outer), _requests(outer), int(align), int(node_limit),
+                                       ctypes.byref(plan)), "memo_dsa_plan_bilevel")
+    out = {name: [arr[i] for i in range(k)] for (name, arr), k in
+           zip(arrs.items(), (len(layer_fwd), len(layer_bwd), nl, nl, len(outer)))}
+    out.update(peak=plan.peak, fwd_peak=plan.fwd_peak, bwd_peak=plan.bwd_peak, optimal=bool(plan.optimal))
     return out

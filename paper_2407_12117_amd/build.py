@@ -13,6 +13,7 @@ LIB = os.path.join(HERE, "libmemo.so")
 SOURCES = {
     "memo_api.cpp": [],
     "memo_sched.cpp": [],
+    "memo_dsa.cpp": [],
     "attn_f32.hip": [],
     "attn_bf16.hip": ["-fno-honor-nans"],
     "recompute_bf16.hip": [],
