@@ -40,7 +40,7 @@ def test_fp32_ragged_and_small(oracle, B, S, H, d):
     _dense_case(oracle, B, S, H, d, "f32", 7 + S)
 
 
-@pytest.mark.parametrize("S", [1, 2, 31, 63, 64, 65, 127, 128, 129, 200, 777])
+@pytest.mark.parametrize("S", [1, 2, 31, 63, 64, 65, 127, 128, 129, 200, 255, 256, 257, 383, 385, 511, 513, 777])
 def test_bf16_small_and_ragged(oracle, S):
     _dense_case(oracle, 2, S, 2, 128, "bf16", 100 + S)
 
