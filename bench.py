@@ -30,9 +30,9 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # figures are carried here per workload; a workload that was not profiled reports null.
 GIB = float(1 << 30)
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "C5": {"attn_fwd_bf16_kernel": (413.0 + 1.02) * GIB,
-           "attn_bwd_dkdv_bf16_kernel": (872.9 + 2.00) * GIB,
-           "attn_bwd_dq_bf16_kernel": (771.9 + 1.00) * GIB},
+    "C5": {"attn_fwd_bf16_kernel": (500.4 + 1.02) * GIB,
+           "attn_bwd_dkdv_bf16_kernel": (699.1 + 2.00) * GIB,
+           "attn_bwd_dq_bf16_kernel": (721.9 + 1.00) * GIB},
 }
 
 
@@ -66,51 +66,14 @@ def cpu_baseline(cfg, q, k, v, g, scale, budget_s=15.0):
                       f"at S={S}, d={d} ({fl / 1e9:.1f} GFLOP in {dt:.1f} s)"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="C5", help="workload C2..C5 (default: the 1M-token one)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-overlap", action="store_true",
-                    help="skip the separate swap/compute overlap measurement (profiling runs)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy kernel (reference for HBM counters)")
-    ap.add_argument("--schedule", default=None, metavar="S[,S...]",
-                    help="instead of the default step: run the two-rounding-buffer schedule over "
-                         "--layers stand-in layers at these sequence lengths and report the exposed "
-                         "copy time per alpha")
-    ap.add_argument("--recompute", default=None, metavar="S",
-                    help="instead of the default step: time the token-wise recomputation kernels "
-                         "(LayerNorm h=4096 and the 4096 -> 1536 projection) on rows [k,S) per alpha")
-    ap.add_argument("--layers", type=int, default=6)
-    ap.add_argument("--alphas", default="0,0.25,0.5,0.75,1")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (one GPU's share of a tensor-parallel layer); "
-              "--gpus above 1 is not supported", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    from paper_2407_12117_amd import binding as mb
-    from paper_2407_12117_amd import synth
-
-    mb.lib()                                             # fail loudly if the HIP library is missing
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.schedule:
-        schedule_bench(torch, mb, synth, args)
-        return
-    if args.recompute:
-        recompute_bench(torch, mb, args)
-        return
-    cfg = synth.CONFIGS[args.config]
+def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, calibrate_copy=False):
+    """One workload: timed steps, per-kernel events, overlap section, CPU baseline.  Returns the JSON object."""
+    cfg = synth.CONFIGS[name]
     assert cfg["dtype"] == "bf16", "bench workloads are the bf16 ones (C2..C5)"
     B, S, H, d = cfg["B"], cfg["S"], cfg["H"], cfg["d"]
     row_bytes, alpha = cfg["act_cols"] * cfg["act_elem"], cfg["alpha"]
     scale = synth.default_scale(d)
-    seed = synth.config_seed(args.config)
+    seed = synth.config_seed(name)
 
     q, k, v, g = synth.attn_inputs(B, S, H, d, "bf16", seed, device="cuda")
     o = torch.empty_like(q)
@@ -145,16 +108,16 @@ def main():
             rec.setdefault("fwd", []).append((f0, f1))
             rec.setdefault("stages", []).append(stages)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     rec = {}
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(rec)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_step = elapsed * 1e3 / steps
 
     pairs = float(S) * float(S)                          # 2 * (S^2/2 causal pairs)
     fwd_flop = 2.0 * pairs * d * H * B
@@ -178,7 +141,7 @@ def main():
     achieved = dom_flop / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
-                "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(args.config, {}).get(dom),
+                "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(name, {}).get(dom),
                 "traffic_unit": "bytes of HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled)",
                 # tensors each kernel must read or write once: fwd Q,K,V,O; dK/dV Q,K,V,dO,dK,dV;
                 # dQ Q,K,V,dO,dQ (the [B,H,S] statistics are 1/64 of a tensor and left out)
@@ -212,23 +175,23 @@ def main():
     def bwd_only():
         mb.memo_attn_bwd(q, k, v, o, lse, g, scale, dq=dq, dk=dk, dv=dv, workspace=ws)
 
-    if args.calibrate_copy:
+    if calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
         dst = torch.empty_like(src)
         dst.copy_(src)                                   # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
-    if args.no_overlap:
+    if not overlap:
         swap = None
     else:
         swap = measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, plan, alpha)
     alpha_solver = solve_alpha_for(mb, S, H, d, fwd_ms * 1e-3,
                                    swap["d2h_GBps"] * 1e9 if swap and swap["d2h_GBps"] else None)
     out = {
-        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: causal attention fwd+bwd B={B} H={H} S={S} d={d} bf16 "
+        "config": {"workload": f"{name}: causal attention fwd+bwd B={B} H={H} S={S} d={d} bf16 "
                                f"N(0,1) q/k/v/dO + token-wise swap of a {S}x{cfg['act_cols']} bf16 "
                                f"activation, alpha={alpha}",
                    "flop_convention": "causal: fwd 2*S^2*d*H, bwd 5*S^2*d*H",
@@ -238,8 +201,64 @@ def main():
         "swap": swap,
         "alpha_solver": alpha_solver,
     }
-    if not args.no_cpu_baseline:
+    if cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, g, scale)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C5", help="workload C2..C5 (default: the 1M-token one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the additional S=256K workload that the default run also times")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="skip the separate swap/compute overlap measurement (profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy kernel (reference for HBM counters)")
+    ap.add_argument("--schedule", default=None, metavar="S[,S...]",
+                    help="instead of the default step: run the two-rounding-buffer schedule over "
+                         "--layers stand-in layers at these sequence lengths and report the exposed "
+                         "copy time per alpha")
+    ap.add_argument("--recompute", default=None, metavar="S",
+                    help="instead of the default step: time the token-wise recomputation kernels "
+                         "(LayerNorm h=4096 and the 4096 -> 1536 projection) on rows [k,S) per alpha")
+    ap.add_argument("--layers", type=int, default=6)
+    ap.add_argument("--alphas", default="0,0.25,0.5,0.75,1")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one GPU's share of a tensor-parallel layer); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2407_12117_amd import binding as mb
+    from paper_2407_12117_amd import synth
+
+    mb.lib()                                             # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.schedule:
+        schedule_bench(torch, mb, synth, args)
+        return
+    if args.recompute:
+        recompute_bench(torch, mb, args)
+        return
+    out = run_workload(torch, mb, synth, args.config, args.steps, args.warmup, overlap=not args.no_overlap,
+                       cpu=not args.no_cpu_baseline, calibrate_copy=args.calibrate_copy)
+    if args.config == "C5" and not args.no_extra:
+        # the metric names S = 256K beside 1M: the 13B-shaped 256K workload, timed the same way (no overlap
+        # section, no CPU leg), rides along in the same line
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        c4 = run_workload(torch, mb, synth, "C4", 3, 1, overlap=False, cpu=False)
+        out["also_measured"] = {"C4": {k: c4[k] for k in ("value", "unit", "ms_per_step", "steps", "warmup")}}
+        out["also_measured"]["C4"]["workload"] = c4["config"]["workload"]
+        out["also_measured"]["C4"]["kernels"] = c4["roofline"]["all_kernels"]
     print(json.dumps(out), flush=True)
 
 
