@@ -299,6 +299,19 @@ memo_status memo_dsa_plan_bilevel(int32_t n_fwd, const memo_dsa_request *layer_f
                                   int32_t n_outer, const memo_dsa_request *outer, int64_t align,
                                   int64_t node_limit, memo_bilevel_plan *out);
 
+/*
+ * Measurement aid (for benchmarks; no part of the method): queues a kernel in which
+ * `workgroups` workgroups of 8 waves each issue iters x 32 bf16 32x32x16 MFMAs on operands
+ * taken from `operands` and nothing else, i.e. workgroups * 8 * iters * 32 * 32768 flop.
+ * Timed by the caller with events on `hip_stream`, it gives the matrix-core rate the chip
+ * sustains on THAT data (it depends on the operand bits through the power limit).
+ *   operands  device, workgroups * 512 * 128 bf16 values (256 bytes per lane), 16-byte aligned
+ *   sink      device, 512 floats, never written in practice
+ * MEMO_ERR_INVALID_ARG on null pointers, workgroups < 1 or iters < 1.
+ */
+memo_status memo_probe_mfma(const void *operands, float *sink, int32_t workgroups, int32_t iters,
+                            void *hip_stream);
+
 /* Pinned host memory helpers (hipHostMalloc / hipHostFree). */
 memo_status memo_host_alloc(void **host_ptr, size_t bytes);
 memo_status memo_host_free(void *host_ptr);

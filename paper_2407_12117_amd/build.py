@@ -17,6 +17,7 @@ SOURCES = {
     "attn_f32.hip": [],
     "attn_bf16.hip": ["-fno-honor-nans"],
     "recompute_bf16.hip": [],
+    "probe_mfma.hip": [],
 }
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -262,6 +262,14 @@ memo_status memo_linear_rows(const void *a, const void *w, const void *bias, voi
     return e == hipSuccess ? MEMO_OK : MEMO_ERR_DEVICE;
 }
 
+memo_status memo_probe_mfma(const void *operands, float *sink, int32_t workgroups, int32_t iters,
+                            void *hip_stream)
+{
+    if (!operands || !sink || workgroups < 1 || iters < 1 || !aligned16(operands)) return MEMO_ERR_INVALID_ARG;
+    const hipError_t e = memo::launch_probe_mfma(operands, sink, workgroups, iters, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MEMO_OK : MEMO_ERR_DEVICE;
+}
+
 memo_status memo_host_alloc(void **host_ptr, size_t bytes)
 {
     if (!host_ptr || bytes == 0) return MEMO_ERR_INVALID_ARG;

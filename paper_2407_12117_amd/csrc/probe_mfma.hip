@@ -1,0 +1,57 @@
+// Measurement aid: the matrix-core rate the chip sustains on given operand data.
+// Every wave loads 8 A and 8 B operands once and then issues only v_mfma_f32_32x32x16_bf16
+// (4 accumulators, no LDS, no other arithmetic): what is timed is the MFMA pipe alone.  On
+// MI355X the result depends on the operand bits (N(0,1) data draws more power than zeros and
+// the clock drops), which is why the benchmark reports it beside the published peak.
+#include "memo_kernels.h"
+#include <hip/hip_bf16.h>
+
+namespace memo {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(512) void probe_mfma_kernel(const __bf16 *data, float *sink, int iters)
+{
+    bf16x8 a[8], b[8];
+    const __bf16 *p = data + ((size_t)blockIdx.x * 512 + threadIdx.x) * 128;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = *reinterpret_cast<const bf16x8 *>(p + i * 8);
+        b[i] = *reinterpret_cast<const bf16x8 *>(p + 64 + i * 8);
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r], b[(r + i) & 7], acc[i], 0, 0, 0);
+        if ((it & 63) == 63)          // keeps the sums finite; 64 multiplies per 2048 MFMAs
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][e] *= 1e-3f;
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    if (s == 12345.678f) sink[threadIdx.x] = s;       // never true in practice: keeps the loop alive
+}
+
+}  // namespace
+
+hipError_t launch_probe_mfma(const void *operands, float *sink, int workgroups, int iters, hipStream_t st)
+{
+    probe_mfma_kernel<<<dim3((unsigned)workgroups), 512, 0, st>>>(static_cast<const __bf16 *>(operands), sink, iters);
+    return hipGetLastError();
+}
+
+}  // namespace memo
