@@ -130,9 +130,14 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
                 for (int e = 0; e < 16; ++e)
                     if (32 * jb + 8 * (e >> 2) + (e & 3) > thr) s[jb][e] = -INFINITY;
         }
-        float mt = fmaxf(s[0][0], s[1][0]);
+        // 32 values in 16 three-input maxima (two chains)
+        float mt = fmaxf(fmaxf(s[0][0], s[0][1]), s[0][2]), mu = fmaxf(fmaxf(s[1][0], s[1][1]), s[1][2]);
 #pragma unroll
-        for (int e = 1; e < 16; ++e) mt = fmaxf(mt, fmaxf(s[0][e], s[1][e]));
+        for (int e = 3; e < 15; e += 2) {
+            mt = fmaxf(fmaxf(mt, s[0][e]), s[0][e + 1]);
+            mu = fmaxf(fmaxf(mu, s[1][e]), s[1][e + 1]);
+        }
+        mt = fmaxf(fmaxf(mt, s[0][15]), fmaxf(mu, s[1][15]));
         mt = max_across_halves(mt);
         // Rescale only when some row of the wave sees a new maximum (rare after the first tiles).
         // Every processed tile has key j0 visible to all 32 rows, so the maximum is finite.
@@ -377,7 +382,8 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
     // The value is loaded raw and only scaled when it is written to LDS a tile later, so that
     // nothing waits for the load (and for the fills queued before it) right after issuing it.
     const float *stat_src = (tid < 64 ? a.lse : a.delta) + stat;
-    const float stat_pad = tid < 64 ? INFINITY : 0.f, stat_mul = tid < 64 ? kLog2e : 1.f;
+    // D_i is kept negated: it then serves as the initial accumulator of dP, and dP - D_i costs nothing
+    const float stat_pad = tid < 64 ? INFINITY : 0.f, stat_mul = tid < 64 ? kLog2e : -1.f;
     auto load_stat = [&](int it) -> float {
         const int64_t r = (int64_t)it * kBq + (tid & 63);
         return (tid < 128 && r < a.S) ? stat_src[r] : stat_pad;
@@ -423,7 +429,13 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
         if (active) {
             const bool diag = i0 < j0w + 31;
             const int thr = (int)(j - i0) - 4 * half; // query offset e' is visible iff e' >= thr
-            f32x16 s, dp;
+            f32x16 s, dp, neg_d;                        // neg_d[e] = -D of query row 8*(e/4) + 4*half + e%4
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * qh + 8 * gq + 4 * half);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) neg_d[4 * gq + r] = d4[r];
+            }
             {
                 // item n: k-chunk n/2 of S (even n: Q rows x K rows) or of dP (odd n: dO rows x V rows)
                 PairSlot ring[3];
@@ -436,7 +448,7 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
                 lds_pipeline_body<16, 2, 2>(ring, issue, [&](auto n, PairSlot &slot) {
                     constexpr int kc = decltype(n)::value / 2, which = decltype(n)::value % 2;
                     if constexpr (which == 0) s = mfma32(slot.a, slot.b, kc == 0 ? zero : s);
-                    else dp = mfma32(slot.a, slot.b, kc == 0 ? zero : dp);
+                    else dp = mfma32(slot.a, slot.b, kc == 0 ? neg_d : dp);
                     if constexpr (decltype(n)::value % 4 == 1) fill_part(IntC<decltype(n)::value / 4>{});
                 });
             }
@@ -452,14 +464,13 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
                 const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * qh + 8 * gq + 4 * half);
-                const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * qh + 8 * gq + 4 * half);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int e = 4 * gq + r;
                     float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[r]));
                     if (diag && (8 * gq + r < thr)) p = 0.f;
                     s[e] = p;
-                    dp[e] = p * (dp[e] - d4[r]);
+                    dp[e] = p * dp[e];                 // dp already holds dP - D_i
                 }
             }
             bf16x8 pB[2], dsB[2];
