@@ -224,7 +224,11 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_bwd_dq_bf16_kernel(AttnAr
     }
     const float c = a.scale * kLog2e;
     const float lse2 = a.lse[stat + iq] * kLog2e;
-    const float Di = a.delta[stat + iq];
+    // -D_i in all 16 registers of an accumulator: dP^T starts from it, so dP - D_i costs nothing
+    const float neg_di = -a.delta[stat + iq];
+    f32x16 neg_d;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) neg_d[e] = neg_di;
 
     f32x16 accQ[4];
 #pragma unroll
@@ -254,39 +258,39 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_bwd_dq_bf16_kernel(AttnAr
         const int thr = (int)(i - (int64_t)jt * kBk) - 4 * half;
         static_for<0, 2>([&](auto jbc) {
             constexpr int jb = decltype(jbc)::value;
-            // S^T and dP^T blocks: item n = (kc = n/2, K or V = n%2), row operands read 4 MFMAs ahead
+            // S^T and dP^T blocks: item n = (kc = n/2, K or V = n%2), row operands read 2 MFMAs ahead
             f32x16 s, dp;
             {
-                bf16x8 ring[5];
+                bf16x8 ring[3];
                 auto issue = [&](auto n, bf16x8 &slot) {
                     constexpr int kc = decltype(n)::value / 2, isv = decltype(n)::value % 2;
                     lds_issue_b128<jb * 8192 + (isv ? vOff : kOff)>(slot, row_addr[kc]);
                 };
-                lds_pipeline_prologue<16, 4, 1>(ring, issue);
-                lds_pipeline_body<16, 4, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
+                lds_pipeline_prologue<16, 2, 1>(ring, issue);
+                lds_pipeline_body<16, 2, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
                     constexpr int kc = decltype(n)::value / 2, isv = decltype(n)::value % 2;
-                    if constexpr (isv) dp = mfma32(slot, gB[kc], kc == 0 ? zero : dp);
+                    if constexpr (isv) dp = mfma32(slot, gB[kc], kc == 0 ? neg_d : dp);
                     else s = mfma32(slot, qB[kc], kc == 0 ? zero : s);
                 });
             }
             // dQ^T += K^T dS^T : A = K^T (transposed read of the same K tile), B = dS^T registers.
             // item n = (sub = n/4, cb = n%4); the first operands are requested before the VALU work
-            TrSlot kring[4];
+            TrSlot kring[3];
             auto k_issue = [&](auto n, TrSlot &slot) {
                 constexpr int sub = decltype(n)::value / 4, cb = decltype(n)::value % 4;
                 lds_issue_tr<(2 * jb + sub) * 4096 + kOff>(slot, tr_addr[cb][0], tr_addr[cb][1]);
             };
-            lds_pipeline_prologue<8, 3, 2>(kring, k_issue);
+            lds_pipeline_prologue<8, 2, 2>(kring, k_issue);
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -lse2));
                 if (diag && (32 * jb + 8 * (e >> 2) + (e & 3) > thr)) p = 0.f;
-                s[e] = p * (dp[e] - Di);           // dS
+                s[e] = p * dp[e];                  // dS (dp already holds dP - D_i)
             }
             bf16x8 dsB[2];
             dsB[0] = pack8(s, 0);
             dsB[1] = pack8(s, 8);
-            lds_pipeline_body<8, 3, 2>(kring, k_issue, [&](auto n, TrSlot &slot) {
+            lds_pipeline_body<8, 2, 2>(kring, k_issue, [&](auto n, TrSlot &slot) {
                 constexpr int sub = decltype(n)::value / 4, cb = decltype(n)::value % 4;
                 accQ[cb] = mfma32(tr_operand(slot), dsB[sub], accQ[cb]);
             });
