@@ -281,10 +281,16 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_bwd_dq_bf16_kernel(AttnAr
                 lds_issue_tr<(2 * jb + sub) * 4096 + kOff>(slot, tr_addr[cb][0], tr_addr[cb][1]);
             };
             lds_pipeline_prologue<8, 2, 2>(kring, k_issue);
+            // the mask sits in a block of its own behind a wave-uniform branch: folded into the loop
+            // below it became a compare and a select per element on every tile
+            if (diag) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (32 * jb + 8 * (e >> 2) + (e & 3) > thr) s[e] = -INFINITY;
+            }
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -lse2));
-                if (diag && (32 * jb + 8 * (e >> 2) + (e & 3) > thr)) p = 0.f;
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -lse2));
                 s[e] = p * dp[e];                  // dS (dp already holds dP - D_i)
             }
             bf16x8 dsB[2];
@@ -465,14 +471,20 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
             };
             lds_pipeline_prologue<16, 2, 2>(tring, t_issue);
             // s, dp: lane = key j, register e = query row i0 + 8*(e/4) + 4*half + e%4
+            // the mask sits in a block of its own behind a wave-uniform branch: folded into the loop
+            // below it became a compare and a select per element on every tile
+            if (diag) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (8 * (e >> 2) + (e & 3) < thr) s[e] = -INFINITY;
+            }
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
                 const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * qh + 8 * gq + 4 * half);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int e = 4 * gq + r;
-                    float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[r]));
-                    if (diag && (8 * gq + r < thr)) p = 0.f;
+                    const float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[r]));
                     s[e] = p;
                     dp[e] = p * dp[e];                 // dp already holds dP - D_i
                 }
