@@ -76,38 +76,46 @@ __global__ __launch_bounds__(256) void layernorm_rows_bf16_kernel(const __bf16 *
 // out[token, feature] = sum_c a[token, c] * w[feature, c] + bias[feature]   (w as [N, K], K contiguous)
 // Workgroup: 8 waves, 256 tokens x 256 features; K streamed in chunks of 64 through a double-buffered
 // LDS ring (32 KB of token rows + 32 KB of weight rows per stage).  The fills are what bounds this
-// kernel (bytes into LDS per MFMA), hence the large tile.  Wave w owns tokens 64*(w%4).. (2 blocks)
-// and features 128*(w/4).. (4 blocks): D[feature, token] = W_rows * A_rows^T, so a lane holds one
-// token and 4 consecutive features per register group (8-byte stores); per 16-wide k-step a wave
-// reads 2 + 4 operands for 8 MFMAs.
+// kernel (bytes into LDS per MFMA), hence the large tile.  Wave w owns tokens 64*(w%4).. (4 blocks
+// of 16) and features 128*(w/4).. (8 blocks of 16): D[feature, token] = W_rows * A_rows^T on
+// v_mfma_f32_16x16x32_bf16, so a lane holds one token and 4 consecutive features per accumulator
+// (8-byte stores); per 32-wide k-step a wave reads 4 + 8 operands for 32 MFMAs.  The 16x16x32
+// shape is chosen over 32x32x16 because the chip is power-limited on random data and sustains
+// about an eighth more flops per second with it; the operand traffic from LDS is the same for
+// the same wave tile.
+//
+// Operand conventions of the 16x16x32 MFMA, D = A(16xK32) * B(K32x16), lane = 16*g4 + l16:
+//   A : lane holds row l16, k = 8*g4 .. 8*g4+7;  B : lane holds col l16, k = 8*g4 .. 8*g4+7;
+//   D : lane holds col l16, rows 4*g4 + r for register r (4 fp32).
 //
 // LDS rows here are 128 bytes (64 bf16): chunk c (16 bytes) of row r sits at position
 // c ^ ((r >> 1) & 7), which keeps 16 lanes reading one chunk column of 16 consecutive rows on
 // distinct banks.  One global_load_lds_dwordx4 moves 8 rows.
-struct SixSlot { bf16x8 b[2], a[4]; };
-
-template <int N>
-__device__ __forceinline__ void lds_wait(SixSlot &x)
-{
-    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
-    asm volatile("s_waitcnt lgkmcnt(%6)"
-                 : "+v"(x.b[0]), "+v"(x.b[1]), "+v"(x.a[0]), "+v"(x.a[1]), "+v"(x.a[2]), "+v"(x.a[3])
-                 : "n"(N));
-}
-
 constexpr int kLinBm = 256, kLinBn = 256, kLinBk = 64;
 constexpr int kLinTile = 256 * 128;          // bytes of one operand's stage
 
+struct TwelveSlot { bf16x8 b[4], a[8]; };
+
+template <int N>
+__device__ __forceinline__ void lds_wait(TwelveSlot &x)
+{
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%12)"
+                 : "+v"(x.b[0]), "+v"(x.b[1]), "+v"(x.b[2]), "+v"(x.b[3]), "+v"(x.a[0]), "+v"(x.a[1]), "+v"(x.a[2]),
+                   "+v"(x.a[3]), "+v"(x.a[4]), "+v"(x.a[5]), "+v"(x.a[6]), "+v"(x.a[7])
+                 : "n"(N));
+}
+
 __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *a, const __bf16 *w, const __bf16 *bias,
-                                                                  __bf16 *out, int64_t row_begin, int64_t row_end,
-                                                                  int K, int N)
+                                                                    __bf16 *out, int64_t row_begin, int64_t row_end,
+                                                                    int K, int N)
 {
     // token rows [buf] in the first 64 KB, weight rows [buf] in the second: each operand's two buffers
     // lie within the 64 KB an LDS immediate offset can reach from one address register
     __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kLinTile];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tb = wave & 3, fh = wave >> 2;
     const int ntn = (N + kLinBn - 1) / kLinBn;
@@ -123,16 +131,15 @@ __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *
     const int64_t m0 = row_begin + mt * kLinBm;
     const int n0 = nt * kLinBn;
 
-    // operand read addresses: row l32 of a 32-row block, chunk 2*kc + half, kc = 0..3
-    uint32_t tok_addr[4], wgt_addr[4];
+    // operand read addresses: row l16 of a 16-row block, chunk 4*ks + g4, ks = 0..1
+    uint32_t tok_addr[2], wgt_addr[2];
 #pragma unroll
-    for (int kc = 0; kc < 4; ++kc) {
-        const uint32_t in_block = (uint32_t)(l32 * 128 + ((((2 * kc + half) ^ ((l32 >> 1) & 7))) << 4));
-        tok_addr[kc] = (uint32_t)(uintptr_t)lds + in_block + (uint32_t)(tb * 64 * 128);
-        wgt_addr[kc] = (uint32_t)(uintptr_t)lds + in_block + (uint32_t)(2 * kLinTile + fh * 128 * 128);
+    for (int ks = 0; ks < 2; ++ks) {
+        const uint32_t in_block = (uint32_t)(l16 * 128 + ((((4 * ks + g4) ^ ((l16 >> 1) & 7))) << 4));
+        tok_addr[ks] = (uint32_t)(uintptr_t)lds + in_block + (uint32_t)(tb * 64 * 128);
+        wgt_addr[ks] = (uint32_t)(uintptr_t)lds + in_block + (uint32_t)(2 * kLinTile + fh * 128 * 128);
     }
     // fills: instruction n of this wave covers stage rows 8*(4*wave + n) + lane/8, position lane%8
-    const bool full_tok = m0 + kLinBm <= row_end, full_wgt = n0 + kLinBn <= N;
     uint32_t tok_off[4], wgt_off[4];
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
@@ -144,7 +151,6 @@ __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *
         tok_off[n] = (uint32_t)((tr - m0) * K * 2 + chunk * 16);
         wgt_off[n] = (uint32_t)((wr - n0) * K * 2 + chunk * 16);
     }
-    (void)full_tok; (void)full_wgt;
     const char *abase = reinterpret_cast<const char *>(a + m0 * K);
     const char *wbase = reinterpret_cast<const char *>(w + (int64_t)n0 * K);
     const int nchunks = K / kLinBk;
@@ -160,13 +166,13 @@ __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *
         }
     };
 
-    f32x16 acc[4][2];                                 // [feature block][token block]
+    f32x4 acc[8][4];                                 // [feature block of 16][token block of 16]
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
+    for (int fb = 0; fb < 8; ++fb)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[cb][t][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[fb][t][e] = 0.f;
 
     fill_chunk(0, 0);
     auto stage = [&](auto bufc, int c) {
@@ -175,23 +181,19 @@ __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *
         wait_fills();
         __syncthreads();          // chunk c is complete; nobody still reads the other buffer
         if (c + 1 < nchunks) fill_chunk(BUF ^ 1, c + 1);
-        SixSlot ring[2];
-        auto issue = [&](auto n, SixSlot &slot) {
-            constexpr int kc = decltype(n)::value;
-            lds_issue_b128<off>(slot.b[0], tok_addr[kc]);
-            lds_issue_b128<off + 32 * 128>(slot.b[1], tok_addr[kc]);
-            lds_issue_b128<off>(slot.a[0], wgt_addr[kc]);
-            lds_issue_b128<off + 32 * 128>(slot.a[1], wgt_addr[kc]);
-            lds_issue_b128<off + 64 * 128>(slot.a[2], wgt_addr[kc]);
-            lds_issue_b128<off + 96 * 128>(slot.a[3], wgt_addr[kc]);
+        TwelveSlot ring[2];
+        auto issue = [&](auto n, TwelveSlot &slot) {
+            constexpr int ks = decltype(n)::value;
+            static_for<0, 4>([&](auto t) { lds_issue_b128<off + decltype(t)::value * 16 * 128>(slot.b[decltype(t)::value], tok_addr[ks]); });
+            static_for<0, 8>([&](auto f) { lds_issue_b128<off + decltype(f)::value * 16 * 128>(slot.a[decltype(f)::value], wgt_addr[ks]); });
         };
-        lds_pipeline_prologue<4, 1, 6>(ring, issue);
-        lds_pipeline_body<4, 1, 6>(ring, issue, [&](auto n, SixSlot &slot) {
+        lds_pipeline_prologue<2, 1, 12>(ring, issue);
+        lds_pipeline_body<2, 1, 12>(ring, issue, [&](auto n, TwelveSlot &slot) {
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb) {
-                acc[cb][0] = mfma32(slot.a[cb], slot.b[0], acc[cb][0]);
-                acc[cb][1] = mfma32(slot.a[cb], slot.b[1], acc[cb][1]);
-            }
+            for (int fb = 0; fb < 8; ++fb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    acc[fb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(slot.a[fb], slot.b[t], acc[fb][t], 0, 0, 0);
         });
     };
     for (int c = 0; c < nchunks; c += 2) {
@@ -199,34 +201,32 @@ __global__ __launch_bounds__(512, 2) void linear_rows_bf16_kernel(const __bf16 *
         if (c + 1 < nchunks) stage(IntC<1>{}, c + 1);
     }
 
-    // acc[cb][t][4g + r] = out[token m0 + 64 tb + 32 t + l32][feature n0 + 128 fh + 32 cb + 8 g + 4 half + r]
+    // acc[fb][t][r] = out[token m0 + 64 tb + 16 t + l16][feature n0 + 128 fh + 16 fb + 4 g4 + r]
     if (n0 + 128 * fh < N) {                          // N is a multiple of 128: a feature half is whole or absent
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int64_t token = m0 + 64 * tb + 32 * t + l32;
+        for (int t = 0; t < 4; ++t) {
+            const int64_t token = m0 + 64 * tb + 16 * t + l16;
             if (token >= row_end) continue;
-            __bf16 *orow = out + token * N + n0 + 128 * fh + 4 * half;
-            const __bf16 *brow = bias ? bias + n0 + 128 * fh + 4 * half : nullptr;
+            __bf16 *orow = out + token * N + n0 + 128 * fh + 4 * g4;
+            const __bf16 *brow = bias ? bias + n0 + 128 * fh + 4 * g4 : nullptr;
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    float b4[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (brow) {
-                        const u32x2 braw = *reinterpret_cast<const u32x2 *>(brow + 32 * cb + 8 * g);
-                        // elements copied to scalars first: a bit cast applied to a vector element
-                        // directly reads element 0 for both with this compiler
-                        const uint32_t r0 = braw[0], r1 = braw[1];
-                        const bf16x2 lo = __builtin_bit_cast(bf16x2, r0), hi = __builtin_bit_cast(bf16x2, r1);
-                        b4[0] = (float)lo[0]; b4[1] = (float)lo[1]; b4[2] = (float)hi[0]; b4[3] = (float)hi[1];
-                    }
-                    f32x2 p = {acc[cb][t][4 * g] + b4[0], acc[cb][t][4 * g + 1] + b4[1]};
-                    f32x2 q = {acc[cb][t][4 * g + 2] + b4[2], acc[cb][t][4 * g + 3] + b4[3]};
-                    u32x2 wv;
-                    wv[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
-                    wv[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(q, bf16x2));
-                    *reinterpret_cast<u32x2 *>(orow + 32 * cb + 8 * g) = wv;
+            for (int fb = 0; fb < 8; ++fb) {
+                float b4[4] = {0.f, 0.f, 0.f, 0.f};
+                if (brow) {
+                    const u32x2 braw = *reinterpret_cast<const u32x2 *>(brow + 16 * fb);
+                    // elements copied to scalars first: a bit cast applied to a vector element
+                    // directly reads element 0 for both with this compiler
+                    const uint32_t r0 = braw[0], r1 = braw[1];
+                    const bf16x2 lo = __builtin_bit_cast(bf16x2, r0), hi = __builtin_bit_cast(bf16x2, r1);
+                    b4[0] = (float)lo[0]; b4[1] = (float)lo[1]; b4[2] = (float)hi[0]; b4[3] = (float)hi[1];
                 }
+                f32x2 p = {acc[fb][t][0] + b4[0], acc[fb][t][1] + b4[1]};
+                f32x2 q = {acc[fb][t][2] + b4[2], acc[fb][t][3] + b4[3]};
+                u32x2 wv;
+                wv[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+                wv[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(q, bf16x2));
+                *reinterpret_cast<u32x2 *>(orow + 16 * fb) = wv;
+            }
         }
     }
 }
