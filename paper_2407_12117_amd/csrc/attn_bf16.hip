@@ -101,17 +101,18 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
         if (jt >= wave_first_tile_masked) return;     // every key of this tile is masked for this wave
 
         // S^T tile: rows = 64 keys (2 blocks of 32), cols = this wave's 32 queries.
-        // item n = (jb = n/8, kc = n%8): one row operand of K, read 4 MFMAs ahead
+        // item n = (jb = n%2, kc = n/2): one row operand of K, read 2 MFMAs ahead; the two key blocks
+        // alternate, so that no MFMA accumulates onto the result of the one issued right before it
         f32x16 s[2];
         {
             bf16x8 ring[3];
             auto issue = [&](auto n, bf16x8 &slot) {
-                constexpr int jb = decltype(n)::value / 8, kc = decltype(n)::value % 8;
+                constexpr int jb = decltype(n)::value % 2, kc = decltype(n)::value / 2;
                 lds_issue_b128<jb * 8192 + kOff>(slot, row_addr[kc]);
             };
             lds_pipeline_prologue<16, 2, 1>(ring, issue);
             lds_pipeline_body<16, 2, 1>(ring, issue, [&](auto n, bf16x8 &slot) {
-                constexpr int jb = decltype(n)::value / 8, kc = decltype(n)::value % 8;
+                constexpr int jb = decltype(n)::value % 2, kc = decltype(n)::value / 2;
                 s[jb] = mfma32(slot, qB[kc], kc == 0 ? zero : s[jb]);
             });
         }
