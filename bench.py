@@ -30,9 +30,9 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # figures are carried here per workload; a workload that was not profiled reports null.
 GIB = float(1 << 30)
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "C5": {"attn_fwd_bf16_kernel": (454.9 + 1.02) * GIB,
-           "attn_bwd_dkdv_bf16_kernel": (747.1 + 2.00) * GIB,
-           "attn_bwd_dq_bf16_kernel": (620.3 + 1.00) * GIB},
+    "C5": {"attn_fwd_bf16_kernel": (404.1 + 1.02) * GIB,
+           "attn_bwd_dkdv_bf16_kernel": (724.8 + 2.00) * GIB,
+           "attn_bwd_dq_bf16_kernel": (631.7 + 1.00) * GIB},
 }
 
 
