@@ -200,6 +200,7 @@ def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, 
         "roofline": roofline,
         "swap": swap,
         "alpha_solver": alpha_solver,
+        "device": device_info(torch),
     }
     if cpu:
         ceil = mfma_ceiling(torch, mb)
@@ -210,6 +211,30 @@ def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, 
                     "power-limited ceiling for this workload is the second figure, not the published peak"}
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, g, scale)
     return out
+
+
+def device_info(torch):
+    """Name, compute-unit count and maximum clock as the runtime reports them, and the dense bf16
+    MFMA peak those give (4096 flop per clock and compute unit) beside the published figure the
+    roofline divides by."""
+    p = torch.cuda.get_device_properties(0)
+    cus = int(p.multi_processor_count)
+    khz = getattr(p, "clock_rate", None)
+    if not khz:                                   # not in this torch's properties: the driver's clock table
+        import glob
+        import re
+        mhz = []
+        for path in glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"):
+            try:
+                mhz += [int(x) for x in re.findall(r"(\d+)\s*Mhz", open(path).read(), re.I)]
+            except OSError:
+                pass
+        khz = max(mhz) * 1000 if mhz else None
+    info = {"name": p.name, "compute_units": cus, "max_clock_MHz": khz / 1e3 if khz else None,
+            "published_bf16_peak_TFLOPs": BF16_MFMA_PEAK_TFLOPS}
+    if khz:
+        info["bf16_peak_from_units_and_clock_TFLOPs"] = cus * khz * 1e3 * 4096 / 1e12
+    return info
 
 
 def main():
