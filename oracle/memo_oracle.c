@@ -285,7 +285,7 @@ int64_t memo_oracle_swap_out(const unsigned char *act, int64_t S, int64_t row_by
     int64_t plan[5];
     if (memo_oracle_swap_plan(S, row_bytes, alpha, plan) != 0) return -1;
     if (plan[2] > host_capacity) return -2;
-    memcpy(host, act, (size_t)plan[2]);
+    if (plan[2] > 0) memcpy(host, act, (size_t)plan[2]);   /* alpha = 0: nothing to copy, host may be NULL */
     return plan[2];
 }
 
@@ -297,7 +297,7 @@ int64_t memo_oracle_swap_in(unsigned char *act, int64_t S, int64_t row_bytes,
     int64_t plan[5];
     if (memo_oracle_swap_plan(S, row_bytes, alpha, plan) != 0) return -1;
     if (plan[2] > host_capacity) return -2;
-    memcpy(act, host, (size_t)plan[2]);
+    if (plan[2] > 0) memcpy(act, host, (size_t)plan[2]);
     return plan[2];
 }
 
