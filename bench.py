@@ -29,6 +29,8 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # (profiles/attn_c5_counters.md).  Counters cannot be read from inside the benchmark, so the
 # figures are carried here per workload; a workload that was not profiled reports null.
 GIB = float(1 << 30)
+TRAFFIC_SOURCE = ("carried from profiles/attn_c5_counters.md (two rocprofv3 --pmc runs of this command), not read "
+                  "in this run; it varies by about +-25 % between runs with the timing of the workgroups")
 MEASURED_HBM_TRAFFIC_BYTES = {
     "C5": {"attn_fwd_bf16_kernel": (404.1 + 1.02) * GIB,
            "attn_bwd_dkdv_bf16_kernel": (724.8 + 2.00) * GIB,
@@ -66,8 +68,37 @@ def cpu_baseline(cfg, q, k, v, g, scale, budget_s=15.0):
                       f"at S={S}, d={d} ({fl / 1e9:.1f} GFLOP in {dt:.1f} s)"}
 
 
-def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, calibrate_copy=False):
-    """One workload: timed steps, per-kernel events, overlap section, CPU baseline.  Returns the JSON object."""
+def parity_check(torch, mb, synth, cfg, q, k, v, g, o, lse, dq, dk, dv, scale, n_rows=12, tail=32):
+    """Bounded check of the tensors one step has just produced against the fp64 oracle, before
+    anything is timed: O, LSE and dQ of uniformly spaced query rows and dK, dV of the last key
+    columns of head 0 (exact oracle rows cost O(i*d) each, so this stays within seconds at 1M)."""
+    import numpy as np
+    from oracle import memo_oracle
+    S = cfg["S"]
+    f64 = lambda t: t.detach().to("cpu").double().numpy()
+    qh, kh, vh, gh = (f64(t[0, :, 0, :]) for t in (q, k, v, g))
+    rows = np.unique(np.concatenate([np.linspace(0, S - 1, n_rows).astype(np.int64), [S // 2 + 77]]))
+    ro, rlse, _, rdq = memo_oracle.head_rows(qh, kh, vh, gh, rows, scale)
+    rdk, rdv = memo_oracle.head_dkdv_tail(qh, kh, vh, gh, S - tail, scale)
+    idx = torch.as_tensor(rows, device=q.device)
+    pairs = {"O": (f64(o[0, idx, 0, :]), ro), "dQ": (f64(dq[0, idx, 0, :]), rdq),
+             "dK": (f64(dk[0, S - tail:, 0, :]), rdk), "dV": (f64(dv[0, S - tail:, 0, :]), rdv)}
+    out = {"rows": len(rows), "tail_columns": tail, "head": 0, "bars": {"max_abs": 2e-2, "rel_l2": 1e-2, "lse_max_abs": 1e-4}}
+    ok = True
+    for name, (got, ref) in pairs.items():
+        err = np.abs(got - ref)
+        rel = float(np.linalg.norm(err) / np.linalg.norm(ref))
+        out[name] = {"max_abs": float(err.max()), "rel_l2": rel}
+        ok = ok and np.isfinite(got).all() and err.max() <= 2e-2 and rel <= 1e-2
+    lse_err = float(np.abs(f64(lse[0, 0, idx]) - rlse).max())
+    out["LSE"] = {"max_abs": lse_err}
+    out["ok"] = bool(ok and lse_err <= 1e-4)
+    return out
+
+
+def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, calibrate_copy=False, parity=True):
+    """One workload: parity check, timed steps, per-kernel events, overlap section, CPU baseline.
+    Returns the JSON object."""
     cfg = synth.CONFIGS[name]
     assert cfg["dtype"] == "bf16", "bench workloads are the bf16 ones (C2..C5)"
     B, S, H, d = cfg["B"], cfg["S"], cfg["H"], cfg["d"]
@@ -108,6 +139,13 @@ def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, 
             rec.setdefault("fwd", []).append((f0, f1))
             rec.setdefault("stages", []).append(stages)
 
+    parity_res = None
+    if parity:
+        # one untimed step, checked against the oracle before anything is timed
+        step()
+        torch.cuda.synchronize()
+        parity_res = parity_check(torch, mb, synth, cfg, q, k, v, g, o, lse, dq, dk, dv, scale)
+        assert parity_res["ok"], f"parity check failed before timing: {parity_res}"
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -143,6 +181,7 @@ def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, 
                 "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                 "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(name, {}).get(dom),
                 "traffic_unit": "bytes of HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled)",
+                "traffic_source": TRAFFIC_SOURCE if MEASURED_HBM_TRAFFIC_BYTES.get(name, {}).get(dom) else None,
                 # tensors each kernel must read or write once: fwd Q,K,V,O; dK/dV Q,K,V,dO,dK,dV;
                 # dQ Q,K,V,dO,dQ (the [B,H,S] statistics are 1/64 of a tensor and left out)
                 "algorithmic_hbm_bytes": {"attn_fwd_bf16_kernel": 4, "attn_bwd_dkdv_bf16_kernel": 6,
@@ -198,6 +237,7 @@ def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, 
                    "frac_of_bf16_mfma_peak": value / BF16_MFMA_PEAK_TFLOPS,
                    "mfu_convention_TFLOPs": 6.0 * pairs * d * H * B / (ms_per_step * 1e-3) / 1e12},
         "roofline": roofline,
+        "parity_before_timing": parity_res,
         "swap": swap,
         "alpha_solver": alpha_solver,
         "device": device_info(torch),
@@ -281,15 +321,20 @@ def main():
     out = run_workload(torch, mb, synth, args.config, args.steps, args.warmup, overlap=not args.no_overlap,
                        cpu=not args.no_cpu_baseline, calibrate_copy=args.calibrate_copy)
     if args.config == "C5" and not args.no_extra:
-        # the metric names S = 256K beside 1M: the 13B-shaped 256K workload, timed the same way (no overlap
-        # section, no CPU leg), rides along in the same line
+        # the metric names S = 256K beside 1M: the 13B-shaped 256K workload and the two shorter ones,
+        # timed the same way (no overlap section, no CPU leg), ride along in the same line
         import gc
-        gc.collect()
-        torch.cuda.empty_cache()
-        c4 = run_workload(torch, mb, synth, "C4", 3, 1, overlap=False, cpu=False)
-        out["also_measured"] = {"C4": {k: c4[k] for k in ("value", "unit", "ms_per_step", "steps", "warmup")}}
-        out["also_measured"]["C4"]["workload"] = c4["config"]["workload"]
-        out["also_measured"]["C4"]["kernels"] = c4["roofline"]["all_kernels"]
+        out["also_measured"] = {}
+        for other, n_steps in (("C4", 3), ("C3", 5), ("C2", 10)):
+            gc.collect()
+            torch.cuda.empty_cache()
+            r = run_workload(torch, mb, synth, other, n_steps, 2, overlap=False, cpu=False)
+            m = {k: r[k] for k in ("value", "unit", "ms_per_step", "steps", "warmup")}
+            m["workload"] = r["config"]["workload"]
+            m["frac_of_bf16_mfma_peak"] = r["config"]["frac_of_bf16_mfma_peak"]
+            m["kernels"] = r["roofline"]["all_kernels"]
+            m["parity_before_timing"] = r["parity_before_timing"]
+            out["also_measured"][other] = m
     print(json.dumps(out), flush=True)
 
 
@@ -298,17 +343,33 @@ def mfma_ceiling(torch, mb, iters=30000):
     but bf16 32x32x16 MFMAs on (a) zeros and (b) N(0,1) operands.  The published peak assumes the
     nominal clock; under the power limit the clock, and with it the attainable rate, depends on the
     operand bits, so the attention kernels (N(0,1) inputs) are bounded by (b), not by the peak."""
+    import ctypes
+    from paper_2407_12117_amd import build as memo_build
+    if not os.path.exists(memo_build.BENCH_AIDS_LIB):
+        memo_build.build_bench_aids()
+    aids = ctypes.CDLL(memo_build.BENCH_AIDS_LIB)
+    aids.memo_bench_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_void_p]
+    aids.memo_bench_probe_mfma.restype = ctypes.c_int
+    sink = torch.zeros(512, dtype=torch.float32, device="cuda")
+
+    def probe(ops, n_iters, workgroups=256):
+        rc = aids.memo_bench_probe_mfma(ops.data_ptr(), sink.data_ptr(), workgroups, n_iters,
+                                        torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, f"memo_bench_probe_mfma failed ({rc})"
+        return float(workgroups) * 8 * n_iters * 32 * 32768.0
+
     out = {}
     gen = torch.Generator(device="cuda").manual_seed(5)
     for name in ("zeros", "normal"):
         n = 256 * 512 * 128
         ops = torch.zeros(n, dtype=torch.bfloat16, device="cuda") if name == "zeros" else \
             torch.randn(n, generator=gen, device="cuda").to(torch.bfloat16)
-        mb.memo_probe_mfma(ops, 200)                       # warm-up
+        probe(ops, 200)                                    # warm-up
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        flop = mb.memo_probe_mfma(ops, iters)
+        flop = probe(ops, iters)
         e1.record()
         torch.cuda.synchronize()
         out[name] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
@@ -338,10 +399,11 @@ def solve_alpha_for(mb, S, H, d, t_fwd_s, bandwidth, n_layers=32, m_cpu=2.0 * 2 
 
 
 def measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, plan, alpha):
-    t_out, t_in = timed(copy_out), timed(copy_in)
-    t_f, t_b = timed(fwd_only), timed(bwd_only)
-    t_f_out = timed(lambda: (copy_out(), fwd_only()))
-    t_b_in = timed(lambda: (copy_in(), bwd_only()))
+    med = lambda fn: sorted(timed(fn) for _ in range(3))[1]     # median of three
+    t_out, t_in = med(copy_out), med(copy_in)
+    t_f, t_b = med(fwd_only), med(bwd_only)
+    t_f_out = med(lambda: (copy_out(), fwd_only()))
+    t_b_in = med(lambda: (copy_in(), bwd_only()))
     nbytes = plan["bytes_swapped"]
     hidden = lambda ta, tc, tac: max(0.0, min(1.0, (ta + tc - tac) / tc)) if tc > 0 else 1.0
     swap = {
@@ -354,6 +416,7 @@ def measure_overlap(torch, mb, timed, copy_out, copy_in, fwd_only, bwd_only, pla
         "hidden_fraction_swap_in": hidden(t_b, t_in, t_b_in),
         "attn_slowdown_fwd": t_f_out / t_f if t_f_out > t_f else 1.0,
         "attn_slowdown_bwd": t_b_in / t_b if t_b_in > t_b else 1.0,
+        "repeats": "median of 3 for every timing above",
     }
 
     return swap
@@ -413,7 +476,8 @@ def schedule_bench(torch, mb, synth, args):
     what three queues that never slow each other would leave exposed given the measured per-layer
     times and copy rates (each swapped layer pays the excess of its copy over the pass it hides
     behind, forward and backward), and the alpha the solver picks for them."""
-    from paper_2407_12117_amd import layer_stack as ls
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import layer_stack as ls                     # the harness of stand-in layers lives beside the tests
     H, d, n = 4, 128, args.layers
     scale = synth.default_scale(d)
     alphas = [float(a) for a in args.alphas.split(",")]

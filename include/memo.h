@@ -50,7 +50,15 @@ typedef enum { MEMO_F32 = 0, MEMO_BF16 = 1 } memo_dtype;
  *            MEMO_F32 with d in {64, 128} (fp32 throughout).
  * S may be any positive length (ragged last tile is handled); causal must be 1.
  * Rows must be 16-byte aligned: base pointers 16-byte aligned and strides a
- * multiple of 8 (bf16) or 4 (fp32) elements.  MEMO_BF16: stride_s <= 2^24 elements.
+ * multiple of 8 (bf16) or 4 (fp32) elements.  MEMO_BF16: stride_s <= 2^24 elements and
+ * ceil(S/128) * H * B < 2^31 (one workgroup per key tile); MEMO_ERR_UNSUPPORTED otherwise.
+ * Non-finite inputs: the kernels keep IEEE semantics, so a NaN or an infinity in q, k, v or d_o
+ * reaches every output element that depends on it: a NaN in key row j makes o, lse, dq of all
+ * query rows i >= j non-finite and, through them, all of dk and dv of that head.  It may also
+ * reach rows that only share a tile with row j (masked probabilities are zeros that still meet
+ * the NaN inside a contraction): rows within the same 256-row block.  Rows outside that block
+ * that do not depend on the value, other heads and other batch entries are bit-identical to a
+ * run without it.
  */
 typedef struct {
     int32_t B, H, d;
@@ -209,6 +217,11 @@ memo_status memo_buffer_plan_make(int64_t S, int32_t n_tensors, const memo_tenso
  *                   stream behind this backward, so it runs under backward(i-1).
  * Calls out of this order give MEMO_ERR_INVALID_ARG and queue nothing.  Nothing blocks
  * the host.  memo_sched_buffer(i) is the device buffer of layer i.
+ * MEMO_ERR_DEVICE from one of the four calls means a HIP call failed part-way: some of that
+ * call's waits and copies may already be queued and its event may not be recorded.  The handle
+ * is then dead (every later call but memo_sched_destroy returns MEMO_ERR_DEVICE): the caller
+ * synchronises its three streams, treats both buffers and the host store as undefined for this
+ * iteration, destroys the handle and starts the iteration again with a new one.
  */
 typedef struct memo_sched memo_sched;
 
@@ -298,19 +311,6 @@ memo_status memo_dsa_plan_bilevel(int32_t n_fwd, const memo_dsa_request *layer_f
                                   const int32_t *fwd_ticks, const int32_t *bwd_ticks,
                                   int32_t n_outer, const memo_dsa_request *outer, int64_t align,
                                   int64_t node_limit, memo_bilevel_plan *out);
-
-/*
- * Measurement aid (for benchmarks; no part of the method): queues a kernel in which
- * `workgroups` workgroups of 8 waves each issue iters x 32 bf16 32x32x16 MFMAs on operands
- * taken from `operands` and nothing else, i.e. workgroups * 8 * iters * 32 * 32768 flop.
- * Timed by the caller with events on `hip_stream`, it gives the matrix-core rate the chip
- * sustains on THAT data (it depends on the operand bits through the power limit).
- *   operands  device, workgroups * 512 * 128 bf16 values (256 bytes per lane), 16-byte aligned
- *   sink      device, 512 floats, never written in practice
- * MEMO_ERR_INVALID_ARG on null pointers, workgroups < 1 or iters < 1.
- */
-memo_status memo_probe_mfma(const void *operands, float *sink, int32_t workgroups, int32_t iters,
-                            void *hip_stream);
 
 /* Pinned host memory helpers (hipHostMalloc / hipHostFree). */
 memo_status memo_host_alloc(void **host_ptr, size_t bytes);

@@ -1,12 +1,13 @@
-// Measurement aid: the matrix-core rate the chip sustains on given operand data.
+// Benchmark aid, built into its own small library (not part of libmemo, not in include/memo.h):
+// the matrix-core rate the chip sustains on given operand data.
 // Every wave loads 8 A and 8 B operands once and then issues only v_mfma_f32_32x32x16_bf16
 // (4 accumulators, no LDS, no other arithmetic): what is timed is the MFMA pipe alone.  On
 // MI355X the result depends on the operand bits (N(0,1) data draws more power than zeros and
 // the clock drops), which is why the benchmark reports it beside the published peak.
-#include "memo_kernels.h"
+#include <hip/hip_runtime.h>
 #include <hip/hip_bf16.h>
+#include <stdint.h>
 
-namespace memo {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -48,10 +49,17 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(const __bf16 *data, flo
 
 }  // namespace
 
-hipError_t launch_probe_mfma(const void *operands, float *sink, int workgroups, int iters, hipStream_t st)
+// Queues a kernel in which `workgroups` workgroups of 8 waves each issue iters x 32 bf16
+// 32x32x16 MFMAs on operands taken from `operands` and nothing else, i.e.
+// workgroups * 8 * iters * 32 * 32768 flop.
+//   operands  device, workgroups * 512 * 128 bf16 values (256 bytes per lane), 16-byte aligned
+//   sink      device, 512 floats, never written in practice
+// Returns 0, 1 on a bad argument, 5 if the launch failed.
+extern "C" int memo_bench_probe_mfma(const void *operands, float *sink, int32_t workgroups, int32_t iters,
+                                     void *hip_stream)
 {
-    probe_mfma_kernel<<<dim3((unsigned)workgroups), 512, 0, st>>>(static_cast<const __bf16 *>(operands), sink, iters);
-    return hipGetLastError();
+    if (!operands || !sink || workgroups < 1 || iters < 1 || (reinterpret_cast<uintptr_t>(operands) & 15u)) return 1;
+    probe_mfma_kernel<<<dim3((unsigned)workgroups), 512, 0, static_cast<hipStream_t>(hip_stream)>>>(
+        static_cast<const __bf16 *>(operands), sink, iters);
+    return hipGetLastError() == hipSuccess ? 0 : 5;
 }
-
-}  // namespace memo

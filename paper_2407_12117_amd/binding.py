@@ -31,7 +31,6 @@ EXPORTS = [
     "memo_sched_buffer", "memo_sched_destroy",
     "memo_layernorm_rows", "memo_linear_rows",
     "memo_trace_to_requests", "memo_dsa_plan", "memo_dsa_plan_bilevel",
-    "memo_probe_mfma",
 ]
 
 
@@ -139,8 +138,6 @@ def lib():
     L.memo_dsa_plan_bilevel.argtypes = [ctypes.c_int32, rp, ctypes.c_int32, rp, ctypes.c_int32, i32p, i32p,
                                         ctypes.c_int32, rp, i64, i64, ctypes.POINTER(MemoBilevelPlan)]
     L.memo_dsa_plan_bilevel.restype = ctypes.c_int
-    L.memo_probe_mfma.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp]
-    L.memo_probe_mfma.restype = ctypes.c_int
     L.memo_layernorm_rows.argtypes = [vp, vp, vp, vp, i64, ctypes.c_int32, ctypes.c_float, i64, i64, vp]
     L.memo_layernorm_rows.restype = ctypes.c_int
     L.memo_linear_rows.argtypes = [vp, vp, vp, vp, i64, ctypes.c_int32, ctypes.c_int32, i64, i64, vp]
@@ -491,13 +488,3 @@ def memo_dsa_plan_bilevel(layer_fwd, layer_bwd, fwd_ticks, bwd_ticks, outer, ali
            zip(arrs.items(), (len(layer_fwd), len(layer_bwd), nl, nl, len(outer)))}
     out.update(peak=plan.peak, fwd_peak=plan.fwd_peak, bwd_peak=plan.bwd_peak, optimal=bool(plan.optimal))
     return out
-
-
-def memo_probe_mfma(operands, iters, workgroups=256, stream=None):
-    """Queues the MFMA-only probe on `operands` (bf16, workgroups*512*128 values); returns its flop count."""
-    if operands.dtype != torch.bfloat16 or not operands.is_contiguous() or operands.numel() < workgroups * 512 * 128:
-        raise ValueError("operands must be a contiguous bf16 tensor of workgroups*512*128 values")
-    sink = torch.zeros(512, dtype=torch.float32, device=operands.device)
-    _check(lib().memo_probe_mfma(operands.data_ptr(), sink.data_ptr(), int(workgroups), int(iters),
-                                 _stream_ptr(stream)), "memo_probe_mfma")
-    return float(workgroups) * 8 * iters * 32 * 32768.0

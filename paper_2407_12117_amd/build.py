@@ -7,17 +7,18 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmemo.so")
-# source -> extra flags.  The bf16 kernels never produce NaNs (masked scores are -inf, and
-# -inf only ever meets finite values), so maxima there need no NaN quieting; the API file keeps
-# full NaN semantics because it validates caller input with isnan().
+# measurement aids of bench.py (an MFMA-only probe): a library of their own, not part of libmemo
+BENCH_AIDS_SRC = os.path.join(HERE, "bench_aids", "probe_mfma.hip")
+BENCH_AIDS_LIB = os.path.join(HERE, "bench_aids", "libmemo_bench_aids.so")
+# source -> extra flags.  Every file keeps IEEE NaN semantics: a NaN or Inf in an input must reach
+# the outputs that depend on it (a training loop detects divergence that way).
 SOURCES = {
     "memo_api.cpp": [],
     "memo_sched.cpp": [],
     "memo_dsa.cpp": [],
     "attn_f32.hip": [],
-    "attn_bf16.hip": ["-fno-honor-nans"],
+    "attn_bf16.hip": [],
     "recompute_bf16.hip": [],
-    "probe_mfma.hip": [],
 }
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -48,6 +49,13 @@ def build(verbose=False, extra=()):
     return LIB
 
 
+def build_bench_aids(verbose=False):
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc] + FLAGS + ["-shared", BENCH_AIDS_SRC, "-o", BENCH_AIDS_LIB], verbose)
+    return BENCH_AIDS_LIB
+
+
 if __name__ == "__main__":
     build(verbose=True, extra=sys.argv[1:])
-    print("built", LIB)
+    build_bench_aids(verbose=True)
+    print("built", LIB, BENCH_AIDS_LIB)

@@ -554,7 +554,7 @@ hipError_t launch_attn_bwd_bf16(const AttnArgs &a, hipStream_t st)
 {
     const int64_t nqt = (a.S + kFwdBq - 1) / kFwdBq;
     const int64_t nkt = (a.S + kBwdBk - 1) / kBwdBk;
-    if (nqt * a.H * a.B > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (nkt * a.H * a.B > 0x7fffffffLL) return hipErrorInvalidValue;   // nkt >= nqt; the front end checks too
     hipError_t e = record_stage(a, 0, st);
     if (e != hipSuccess) return e;
     if ((e = launch_attn_delta(a, true, st)) != hipSuccess) return e;

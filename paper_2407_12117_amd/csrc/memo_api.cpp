@@ -27,6 +27,8 @@ memo_status check_desc(const memo_attn_desc *d, memo::AttnArgs *out)
     if (d->stride_b % vec || d->stride_s % vec || d->stride_h % vec) return MEMO_ERR_UNSUPPORTED;
     // the tile index arithmetic is 64-bit; the row count per launch must fit the grid
     if (d->S > ((int64_t)1 << 31) - 1024) return MEMO_ERR_UNSUPPORTED;
+    // one workgroup per 128-key tile (dK/dV kernel; the other bf16 kernels launch half as many)
+    if (d->dtype == MEMO_BF16 && ((d->S + 127) / 128) * d->H * d->B > 0x7fffffffLL) return MEMO_ERR_UNSUPPORTED;
     // the bf16 tile fills address 64 rows with 32-bit per-lane byte offsets
     if (d->dtype == MEMO_BF16 && d->stride_s > ((int64_t)1 << 24)) return MEMO_ERR_UNSUPPORTED;
     std::memset(out, 0, sizeof(*out));
@@ -259,14 +261,6 @@ memo_status memo_linear_rows(const void *a, const void *w, const void *bias, voi
     if (!aligned16(a) || !aligned16(w) || !aligned16(out) || (bias && !aligned16(bias))) return MEMO_ERR_UNSUPPORTED;
     const hipError_t e = memo::launch_linear_rows_bf16(a, w, bias, out, row_begin, row_end, K, N,
                                                        static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? MEMO_OK : MEMO_ERR_DEVICE;
-}
-
-memo_status memo_probe_mfma(const void *operands, float *sink, int32_t workgroups, int32_t iters,
-                            void *hip_stream)
-{
-    if (!operands || !sink || workgroups < 1 || iters < 1 || !aligned16(operands)) return MEMO_ERR_INVALID_ARG;
-    const hipError_t e = memo::launch_probe_mfma(operands, sink, workgroups, iters, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MEMO_OK : MEMO_ERR_DEVICE;
 }
 

@@ -46,7 +46,4 @@ hipError_t launch_layernorm_rows_bf16(const void *x, const void *gamma, const vo
 hipError_t launch_linear_rows_bf16(const void *a, const void *w, const void *bias, void *out,
                                    int64_t row_begin, int64_t row_end, int K, int N, hipStream_t st);
 
-// Measurement aid: `workgroups` x 8 waves issue iters x 32 MFMAs each on the operands given.
-hipError_t launch_probe_mfma(const void *operands, float *sink, int workgroups, int iters, hipStream_t st);
-
 }  // namespace memo

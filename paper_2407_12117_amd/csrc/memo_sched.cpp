@@ -28,6 +28,9 @@ struct memo_sched {
     std::vector<hipEvent_t> fwd_done, offloaded, bwd_done, fetched;
     // position in the fixed call sequence of one iteration, 0 .. 4n-1
     int64_t pos = 0;
+    // set when a HIP call failed inside a schedule call: some of that call's work may already be
+    // queued, so the handle refuses every later call except memo_sched_destroy
+    bool failed = false;
 
     bool swapped(int32_t layer) const { return layer < n_layers - 2; }
 };
@@ -53,10 +56,17 @@ bool create_events(std::vector<hipEvent_t> &v, int32_t n)
 memo_status take_position(memo_sched *s, int32_t layer, bool backward, bool end)
 {
     if (!s || layer < 0 || layer >= s->n_layers) return MEMO_ERR_INVALID_ARG;
+    if (s->failed) return MEMO_ERR_DEVICE;
     const int64_t n = s->n_layers;
     const int64_t want = (backward ? 2 * n + 2 * (n - 1 - layer) : 2 * static_cast<int64_t>(layer)) + (end ? 1 : 0);
     if (s->pos != want) return MEMO_ERR_INVALID_ARG;
     return MEMO_OK;
+}
+
+memo_status fail(memo_sched *s)
+{
+    s->failed = true;
+    return MEMO_ERR_DEVICE;
 }
 
 void advance(memo_sched *s) { s->pos = (s->pos + 1) % (4 * static_cast<int64_t>(s->n_layers)); }
@@ -137,7 +147,7 @@ memo_status memo_sched_forward_begin(memo_sched *s, int32_t layer)
     if (st != MEMO_OK) return st;
     // Buffer layer%2 was last read by the offload of layer-2: do not overwrite it earlier.
     if (layer >= 2 && hipStreamWaitEvent(s->compute, s->offloaded[layer - 2], 0) != hipSuccess)
-        return MEMO_ERR_DEVICE;
+        return fail(s);
     advance(s);
     return MEMO_OK;
 }
@@ -147,18 +157,18 @@ memo_status memo_sched_forward_end(memo_sched *s, int32_t layer)
     memo_status st = take_position(s, layer, false, true);
     if (st != MEMO_OK) return st;
     if (s->swapped(layer)) {
-        if (hipEventRecord(s->fwd_done[layer], s->compute) != hipSuccess) return MEMO_ERR_DEVICE;
+        if (hipEventRecord(s->fwd_done[layer], s->compute) != hipSuccess) return fail(s);
         if (hipStreamWaitEvent(s->offload, s->fwd_done[layer], 0) != hipSuccess)
-            return MEMO_ERR_DEVICE;
+            return fail(s);
         const char *buf = s->buffer[layer % 2];
         char *slot = s->host + static_cast<size_t>(layer) * s->host_bytes;
         for (const memo_tensor_slot &t : s->slots) {
             if (t.bytes_swapped == 0) continue;
             if (hipMemcpyAsync(slot + t.host_offset, buf + t.dev_offset, t.bytes_swapped,
                                hipMemcpyDeviceToHost, s->offload) != hipSuccess)
-                return MEMO_ERR_DEVICE;
+                return fail(s);
         }
-        if (hipEventRecord(s->offloaded[layer], s->offload) != hipSuccess) return MEMO_ERR_DEVICE;
+        if (hipEventRecord(s->offloaded[layer], s->offload) != hipSuccess) return fail(s);
     }
     advance(s);
     return MEMO_OK;
@@ -169,7 +179,7 @@ memo_status memo_sched_backward_begin(memo_sched *s, int32_t layer)
     memo_status st = take_position(s, layer, true, false);
     if (st != MEMO_OK) return st;
     if (s->swapped(layer) && hipStreamWaitEvent(s->compute, s->fetched[layer], 0) != hipSuccess)
-        return MEMO_ERR_DEVICE;
+        return fail(s);
     advance(s);
     return MEMO_OK;
 }
@@ -182,18 +192,18 @@ memo_status memo_sched_backward_end(memo_sched *s, int32_t layer)
     if (j >= 0) {
         // Buffer layer%2 is dead once this backward has finished: fetch layer j into it.
         // Layer j's offload finished long ago: forward(j+2) waited for it.
-        if (hipEventRecord(s->bwd_done[layer], s->compute) != hipSuccess) return MEMO_ERR_DEVICE;
+        if (hipEventRecord(s->bwd_done[layer], s->compute) != hipSuccess) return fail(s);
         if (hipStreamWaitEvent(s->prefetch, s->bwd_done[layer], 0) != hipSuccess)
-            return MEMO_ERR_DEVICE;
+            return fail(s);
         char *buf = s->buffer[j % 2];
         const char *slot = s->host + static_cast<size_t>(j) * s->host_bytes;
         for (const memo_tensor_slot &t : s->slots) {
             if (t.bytes_swapped == 0) continue;
             if (hipMemcpyAsync(buf + t.dev_offset, slot + t.host_offset, t.bytes_swapped,
                                hipMemcpyHostToDevice, s->prefetch) != hipSuccess)
-                return MEMO_ERR_DEVICE;
+                return fail(s);
         }
-        if (hipEventRecord(s->fetched[j], s->prefetch) != hipSuccess) return MEMO_ERR_DEVICE;
+        if (hipEventRecord(s->fetched[j], s->prefetch) != hipSuccess) return fail(s);
     }
     advance(s);
     return MEMO_OK;

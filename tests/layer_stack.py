@@ -1,55 +1,49 @@
-"""A stack of stand-in transformer layers that drives the rounding-buffer schedule
-(Section 4.1, Figure 5; Section 4.3.4).
+"""Test and benchmark harness (not part of the library): a stack of stand-in transformer layers
+that drives the rounding-buffer schedule (Section 4.1, Figure 5; Section 4.3.4) together with the
+token-wise recomputation kernels.
 
-Each layer is   q, k, v = a_q*x, a_k*rot(x, 37), a_v*rot(x, 74) ;  o = causal_attention(q, k, v) ;
-x' = x + o,   with per-layer scalars a_* and rot = rotation of a token's feature vector (so that
-q_i and k_i are not parallel, which would put all the softmax mass on the diagonal): the
-token-wise producers stand in for LayerNorm + QKV projection (any row of q, k, v can be
-regenerated from the same row of x), the attention is the real kernel.  Saved tensors of a layer, all [S, H*d] bf16 in one rounding buffer:
-    0 input x (alpha 1)   1 o (alpha 1)   2..4 q, k, v (alpha)   5.. filler (alpha)
-The filler tensors bring the layer to the 16 x (b*s*h) of Section 4.1 (norm outputs, MLP
-activations, ...): they are copied like the rest but nothing reads them.  The logsumexp
-([H,S] fp32 per layer, 1/256 of a layer's bytes at d = 128) stays on the device.
+Each layer is   norm = LayerNorm(x) ;  q, k, v = norm W_q^T + b_q, ... ;  o = causal_attention(q, k, v) ;
+x' = x + o,   with per-layer gamma, beta, W_* [h, h], b_* drawn from a seed (h = H*d).  LayerNorm,
+the projections, the attention and the schedule are libmemo's (memo_layernorm_rows,
+memo_linear_rows, memo_attn_fwd/bwd, memo_sched_*); the residual add and the stand-in gradient
+propagation below are torch arithmetic of this harness.  Saved tensors of a layer, all [S,h] bf16
+in one rounding buffer:
+    0 input x (alpha 1)   1 o (alpha 1)   2 norm (alpha)   3..5 q, k, v (alpha)   6.. filler (alpha)
+which with 10 fillers is the 16 x (b*s*h) of Section 4.1 (MLP activations and the like: they are
+copied like the rest but nothing reads them).  The logsumexp ([H,S] fp32 per layer, 1/256 of a
+layer's bytes at d = 128) stays on the device.
 
-The caller-side arithmetic here (scalar multiplies, adds) is torch; attention and the
-schedule are libmemo's.  There is no CPU fallback.
+Backward of a layer: rows [0,k) of norm, q, k, v come back from the host with the prefetch, rows
+[k,S) are rebuilt from the stored layer input by the same kernels on that row range (the paper's
+token-wise recomputation), then memo_attn_bwd runs.  The gradient that is passed down is a stand-in:
+dx' = dx + dq W_q + dk W_k + dv W_v (the projections' input gradient, LayerNorm treated as
+identity); the weight gradients and the LayerNorm Jacobian are outside this path.  What the tests
+need from it is that every regenerated row feeds the result.  There is no CPU fallback.
 """
 import torch
 
-from . import binding as mb
+from paper_2407_12117_amd import binding as mb
 
-N_SAVED = 16          # tensors per layer, Section 4.1: 16*b*s*h elements in all
+N_SAVED = 16          # saved [S,h] tensors per layer, Section 4.1: 16*b*s*h elements in all
+EPS = 1e-5
 
 
 def layer_tensors(H, d, alpha, n_saved=N_SAVED):
+    """(row_bytes, alpha) of a layer's saved tensors."""
+    if n_saved < 6:
+        raise ValueError("a layer saves at least x, o, norm, q, k, v")
     row = H * d * 2
     return [(row, 1.0), (row, 1.0)] + [(row, float(alpha))] * (n_saved - 2)
 
 
-def layer_scalars(layer):
-    """a_q, a_k, a_v of a layer: exact in bf16, different per layer."""
-    return 1.0 + 0.125 * (layer % 3), 1.0 - 0.0625 * (layer % 5), 0.75 + 0.125 * (layer % 4)
-
-
-SHIFTS = (0, 37, 74)   # feature rotation of q, k, v
-
-
-def produce(x_rows, a, shift, out_rows):
-    """out = a * rot(x, shift), row by row (token-wise)."""
-    if shift == 0:
-        torch.mul(x_rows, a, out=out_rows)
-    else:
-        torch.mul(x_rows[:, shift:], a, out=out_rows[:, :-shift])
-        torch.mul(x_rows[:, :shift], a, out=out_rows[:, -shift:])
-
-
-def accumulate(dx, g, a, shift):
-    """dx += a * rot^-1(g): the backward of produce."""
-    if shift == 0:
-        dx.add_(g, alpha=a)
-    else:
-        dx[:, shift:].add_(g[:, :-shift], alpha=a)
-        dx[:, :shift].add_(g[:, -shift:], alpha=a)
+def layer_params(layer, h, device):
+    """gamma, beta [h] and (W [h,h], b [h]) for q, k, v of a layer, bf16, from a per-layer seed."""
+    g = torch.Generator().manual_seed(9000 + layer)
+    gamma = (1.0 + 0.1 * torch.randn(h, generator=g)).to(torch.bfloat16).to(device)
+    beta = (0.1 * torch.randn(h, generator=g)).to(torch.bfloat16).to(device)
+    proj = [((torch.randn((h, h), generator=g) / h ** 0.5).to(torch.bfloat16).to(device),
+             (0.1 * torch.randn(h, generator=g)).to(torch.bfloat16).to(device)) for _ in range(3)]
+    return gamma, beta, proj
 
 
 class LayerStack:
@@ -64,7 +58,10 @@ class LayerStack:
         copies and compute, so a caller that builds many stacks should create the streams once."""
         if d != 128:
             raise ValueError("the bf16 attention path needs d = 128")
+        if (H * d) % 512:
+            raise ValueError("memo_layernorm_rows needs a hidden size that is a multiple of 512 (H % 4 == 0)")
         self.n, self.S, self.H, self.d, self.scale, self.swap = n_layers, S, H, d, scale, swap
+        self.h = H * d
         self.tensors = layer_tensors(H, d, alpha, n_saved)
         self.slots, self.dev_bytes, self.host_bytes = mb.memo_buffer_plan_make(S, self.tensors)
         dev = torch.device(device)
@@ -75,6 +72,7 @@ class LayerStack:
         self.buffers = [torch.empty(self.dev_bytes, dtype=torch.uint8, device=dev)
                         for _ in range(n_buf)]
         self.lse = [torch.empty((1, H, S), dtype=torch.float32, device=dev) for _ in range(n_layers)]
+        self.params = [layer_params(i, self.h, dev) for i in range(n_layers)]
         self.sched = None
         self.host = None
         if swap:
@@ -83,12 +81,11 @@ class LayerStack:
                 torch.empty(max(held, 256), dtype=torch.uint8, pin_memory=True)
             self.sched = mb.MemoSched(n_layers, S, self.tensors, self.buffers, self.host,
                                       self.compute, self.offload, self.prefetch)
-        shape = (S, H * d)
+        shape = (S, self.h)
         self.x_io = [torch.empty(shape, dtype=torch.bfloat16, device=dev) for _ in range(2)]
         self.grads = [torch.empty((1, S, H, d), dtype=torch.bfloat16, device=dev) for _ in range(3)]
         self.dx = torch.empty(shape, dtype=torch.bfloat16, device=dev)
-        probe = self.grads[0]
-        self.workspace = torch.empty(max(256, mb.memo_attn_bwd_workspace_bytes(probe, scale)),
+        self.workspace = torch.empty(max(256, mb.memo_attn_bwd_workspace_bytes(self.grads[0], scale)),
                                      dtype=torch.uint8, device=dev)
 
     # ---- views into a layer's buffer
@@ -115,12 +112,14 @@ class LayerStack:
             for i in range(self.n):
                 if self.sched:
                     self.sched.forward_begin(i)
-                x, o = self.view(i, 0), self.view(i, 1)
+                x, o, norm = (self.view(i, t) for t in range(3))
+                gamma, beta, proj = self.params[i]
                 x.copy_(cur)
-                for t, a, sh in zip((2, 3, 4), layer_scalars(i), SHIFTS):
-                    produce(x, a, sh, self.view(i, t))
-                mb.memo_attn_fwd(self._heads(self.view(i, 2)), self._heads(self.view(i, 3)),
-                                 self._heads(self.view(i, 4)), self.scale, o=self._heads(o),
+                mb.memo_layernorm_rows(x, gamma, beta, EPS, y=norm, stream=self.compute)
+                for t, (w, b) in zip((3, 4, 5), proj):
+                    mb.memo_linear_rows(norm, w, b, out=self.view(i, t), stream=self.compute)
+                mb.memo_attn_fwd(self._heads(self.view(i, 3)), self._heads(self.view(i, 4)),
+                                 self._heads(self.view(i, 5)), self.scale, o=self._heads(o),
                                  lse=self.lse[i], stream=self.compute)
                 nxt = self.x_io[(i + 1) % 2]
                 torch.add(x, o, out=nxt)
@@ -141,21 +140,23 @@ class LayerStack:
             for i in range(self.n - 1, -1, -1):
                 if self.sched:
                     self.sched.backward_begin(i)
-                x, o = self.view(i, 0), self.view(i, 1)
-                scal = layer_scalars(i)
+                x, o, norm = (self.view(i, t) for t in range(3))
+                gamma, beta, proj = self.params[i]
                 if self.sched and i < self.n - 2:
-                    for t, a, sh in zip((2, 3, 4), scal, SHIFTS):
-                        k = self.slots[t]["k_swapped"]
-                        if k < self.S:
-                            produce(x[k:], a, sh, self.view(i, t)[k:])
+                    # token-wise recomputation: rows [k,S) of norm from x, then of q, k, v from norm
+                    mb.memo_layernorm_rows(x, gamma, beta, EPS, y=norm, rows=(self.slots[2]["k_swapped"], self.S),
+                                           stream=self.compute)
+                    for t, (w, b) in zip((3, 4, 5), proj):
+                        mb.memo_linear_rows(norm, w, b, out=self.view(i, t),
+                                            rows=(self.slots[t]["k_swapped"], self.S), stream=self.compute)
                 if on_layer is not None:
                     on_layer(i)
-                mb.memo_attn_bwd(self._heads(self.view(i, 2)), self._heads(self.view(i, 3)),
-                                 self._heads(self.view(i, 4)), self._heads(o), self.lse[i],
+                mb.memo_attn_bwd(self._heads(self.view(i, 3)), self._heads(self.view(i, 4)),
+                                 self._heads(self.view(i, 5)), self._heads(o), self.lse[i],
                                  self._heads(dx), self.scale, dq=dq, dk=dk, dv=dv,
                                  workspace=self.workspace, stream=self.compute)
-                for g, a, sh in zip((dq, dk, dv), scal, SHIFTS):
-                    accumulate(dx, g.view(self.S, self.H * self.d), a, sh)
+                for g, (w, _) in zip((dq, dk, dv), proj):
+                    dx.addmm_(g.view(self.S, self.h), w)
                 if self.sched:
                     self.sched.backward_end(i)
             return dx

@@ -15,10 +15,10 @@ import torch
 
 from oracle import memo_sched_oracle as so
 from paper_2407_12117_amd import binding as mb
-from paper_2407_12117_amd import layer_stack as ls
 from paper_2407_12117_amd import synth
 
 import gpu_util as gu
+import layer_stack as ls
 
 pytestmark = pytest.mark.gpu
 
@@ -70,8 +70,8 @@ def test_backward_finds_what_the_oracle_replay_gives(n_layers, S, tensors):
     sched.destroy()
 
 
-@pytest.mark.parametrize("n_layers,S,H,alpha", [(4, 640, 2, 0.5), (5, 1100, 1, 0.3), (3, 384, 4, 0.0),
-                                                 (4, 512, 2, 1.0)])
+@pytest.mark.parametrize("n_layers,S,H,alpha", [(4, 640, 4, 0.5), (5, 1100, 4, 0.3), (3, 384, 8, 0.0),
+                                                 (4, 512, 4, 1.0)])
 def test_swapped_stack_equals_resident_stack(oracle, n_layers, S, H, alpha):
     print(f"[case] sched stack n={n_layers} S={S} H={H} alpha={alpha}", flush=True)
     d, scale = 128, synth.default_scale(128)
@@ -89,7 +89,8 @@ def test_swapped_stack_equals_resident_stack(oracle, n_layers, S, H, alpha):
         def grab(i, st=st, swap=swap):
             if swap and i == 0:
                 # what the first layer's backward is about to read, dropped rows regenerated
-                captured["qkvo"] = [st.view(0, t).clone() for t in (2, 3, 4, 1)]
+                captured["qkvo"] = [st.view(0, t).clone() for t in (3, 4, 5, 1)]
+                captured["x_norm"] = [st.view(0, t).clone() for t in (0, 2)]
                 captured["lse"] = st.lse[0].clone()
                 captured["d_o"] = st.dx.clone()
         torch.cuda.synchronize()
@@ -104,6 +105,18 @@ def test_swapped_stack_equals_resident_stack(oracle, n_layers, S, H, alpha):
     assert torch.equal(results[True][0], results[False][0])
     assert torch.equal(results[True][1], results[False][1])
     assert torch.isfinite(results[True][1].float()).all()
+
+    # what layer 0's backward found in its buffer after prefetch + token-wise recomputation, against
+    # the recomputation oracle run on the stored layer input alone (rows [0,k) came from the host,
+    # rows [k,S) from the LayerNorm and projection kernels)
+    from oracle import memo_recompute_oracle as ro
+    x_in, norm = (gu.to_f64(t) for t in captured["x_norm"])
+    assert np.array_equal(x_in, gu.to_f64(x0))
+    gamma, beta, proj = ls.layer_params(0, H * d, "cpu")
+    ref_norm = ro.layernorm(x_in, gu.to_f64(gamma), gu.to_f64(beta), ls.EPS)
+    gu.assert_close("norm", norm, ref_norm, "bf16", scaled=True)
+    for name, got, (w, b) in zip("qkv", captured["qkvo"][:3], proj):
+        gu.assert_close(name, gu.to_f64(got), ro.linear(ref_norm, gu.to_f64(w), gu.to_f64(b)), "bf16", scaled=True)
 
     # layer 0 of the swapped run against the fp64 oracle, on the very tensors it was fed
     q, k, v, o = [gu.to_f64(t).reshape(1, S, H, d) for t in captured["qkvo"]]
