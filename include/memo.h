@@ -108,6 +108,23 @@ memo_status memo_attn_bwd_staged(const memo_attn_desc *desc, const void *q, cons
                                  void *const *stage_events);
 
 /*
+ * memo_attn_bwd for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as memo_attn_bwd without the workspace: the D_i buffer lives in a static
+ * device array inside the library (16 MiB per GPU the library runs on, held until the process
+ * ends), so the call allocates nothing, on the device or through any library.
+ * Limit: B * H * S <= MEMO_ATTN_BWD_STATIC_MAX_ROWS, else MEMO_ERR_WORKSPACE and nothing is queued.
+ * Every call on one GPU uses that GPU's one array: calls that may overlap in time on the same GPU
+ * (different streams, different host threads) race and must be serialised by the caller.  The
+ * array keeps the previous call's contents; the backward overwrites what it reads, so no clearing
+ * is needed.  The device must be the current one, as for every other entry point.
+ */
+#define MEMO_ATTN_BWD_STATIC_MAX_ROWS ((size_t)4 << 20)
+memo_status memo_attn_bwd_static(const memo_attn_desc *desc, const void *q, const void *k,
+                                 const void *v, const void *o, const float *lse, const void *d_o,
+                                 void *dq, void *dk, void *dv, void *stream);
+
+/*
  * Token split (Section 4.1, "at the token granularity ... we offload a fraction alpha
  * to CPU, while the remaining part is discarded").  k = floor(alpha * S) evaluated in
  * IEEE double; tokens [0,k) are swapped, tokens [k,S) are recomputed by the caller

@@ -23,6 +23,7 @@ MEMO_BF16 = 1
 
 EXPORTS = [
     "memo_attn_fwd", "memo_attn_bwd_workspace_bytes", "memo_attn_bwd", "memo_attn_bwd_staged",
+    "memo_attn_bwd_static",
     "memo_split_tokens",
     "memo_swap_plan_make", "memo_swap_out", "memo_swap_in", "memo_solve_alpha",
     "memo_host_alloc", "memo_host_free", "memo_status_str",
@@ -98,6 +99,8 @@ def lib():
     L.memo_attn_bwd_staged.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
                                        ctypes.POINTER(ctypes.c_void_p)]
     L.memo_attn_bwd_staged.restype = ctypes.c_int
+    L.memo_attn_bwd_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.memo_attn_bwd_static.restype = ctypes.c_int
     L.memo_split_tokens.argtypes = [i64, f64]
     L.memo_split_tokens.restype = i64
     L.memo_swap_plan_make.argtypes = [i64, i64, f64, ctypes.POINTER(MemoSwapPlan)]
@@ -253,6 +256,18 @@ def memo_attn_bwd(q, k, v, o, lse, d_o, scale, dq=None, dk=None, dv=None, worksp
         handles = (ctypes.c_void_p * 4)(*[_event_ptr(e, _stream_obj(stream)) for e in stage_events])
         st = lib().memo_attn_bwd_staged(*args, handles)
     _check(st, "memo_attn_bwd")
+    return dq, dk, dv
+
+
+def memo_attn_bwd_static(q, k, v, o, lse, d_o, scale, dq, dk, dv, stream=None):
+    """memo_attn_bwd without a workspace and without any allocation: the caller passes every
+    output; the library keeps D_i in its static device array (B*H*S <= 4 Mi rows)."""
+    _same_layout(q, k, v, o, d_o, dq, dk, dv)
+    desc = make_desc(q, scale)
+    _check(lib().memo_attn_bwd_static(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                      o.data_ptr(), lse.data_ptr(), d_o.data_ptr(), dq.data_ptr(),
+                                      dk.data_ptr(), dv.data_ptr(), _stream_ptr(stream)),
+           "memo_attn_bwd_static")
     return dq, dk, dv
 
 

@@ -18,6 +18,7 @@ SOURCES = {
     "memo_dsa.cpp": [],
     "attn_f32.hip": [],
     "attn_bf16.hip": [],
+    "attn_bwd_static.hip": [],
     "recompute_bf16.hip": [],
 }
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
