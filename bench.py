@@ -297,6 +297,9 @@ def main():
     ap.add_argument("--recompute", default=None, metavar="S",
                     help="instead of the default step: time the token-wise recomputation kernels "
                          "(LayerNorm h=4096 and the 4096 -> 1536 projection) on rows [k,S) per alpha")
+    ap.add_argument("--atomic-probe", action="store_true",
+                    help="instead of the default step: measure the fp32 atomic-add rate in the access pattern a "
+                         "fused backward (dQ through atomics) would produce, and what that costs at C3 and C5")
     ap.add_argument("--layers", type=int, default=6)
     ap.add_argument("--alphas", default="0,0.25,0.5,0.75,1")
     args = ap.parse_args()
@@ -318,6 +321,9 @@ def main():
     if args.recompute:
         recompute_bench(torch, mb, args)
         return
+    if args.atomic_probe:
+        atomic_probe(torch)
+        return
     out = run_workload(torch, mb, synth, args.config, args.steps, args.warmup, overlap=not args.no_overlap,
                        cpu=not args.no_cpu_baseline, calibrate_copy=args.calibrate_copy)
     if args.config == "C5" and not args.no_extra:
@@ -338,16 +344,58 @@ def main():
     print(json.dumps(out), flush=True)
 
 
+def bench_aids():
+    import ctypes
+    from paper_2407_12117_amd import build as memo_build
+    if not os.path.exists(memo_build.BENCH_AIDS_LIB):
+        memo_build.build_bench_aids()
+    return ctypes.CDLL(memo_build.BENCH_AIDS_LIB)
+
+
+def atomic_probe(torch):
+    """What a fused five-contraction backward would pay for dQ: a key-stationary workgroup (128 keys) has a
+    64 x 128 fp32 partial dQ (32 KB) to add to global memory per query tile step.  Measures the chip's rate
+    for exactly that pattern and prices the atomics alone at C3 and C5 against the dQ kernel they would replace."""
+    import ctypes
+    aids = bench_aids()
+    aids.memo_bench_atomic_add.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+    heads, nblocks = 4, 1 << 14                          # per head 16384 blocks of 32 KB: S = 1M rows of 128 fp32
+    buf = torch.zeros(heads * nblocks * 8192, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for scope, sname in ((0, "device-scope atomic add"), (1, "workgroup-scope atomic add"), (2, "plain store")):
+        for wgs in (256, 2048):
+            for dup in (1, 4):
+                iters = 2000
+                assert aids.memo_bench_atomic_add(buf.data_ptr(), nblocks, heads, wgs, 10, dup, nblocks, scope, st) == 0
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                assert aids.memo_bench_atomic_add(buf.data_ptr(), nblocks, heads, wgs, iters, dup, nblocks, scope, st) == 0
+                e1.record()
+                torch.cuda.synchronize()
+                byt = wgs * iters * dup * 32768.0
+                rows.append({"op": sname, "workgroups": wgs, "partials_per_block": dup,
+                             "TB_per_s": byt / (e0.elapsed_time(e1) * 1e-3) / 1e12})
+    rate = max(r["TB_per_s"] for r in rows if r["op"] == "device-scope atomic add") * 1e12
+    cost = {}
+    for name, S, H in (("C3", 131072, 4), ("C5", 1048576, 4)):
+        steps = (S / 128.0) * (S / 64.0) / 2.0 * H       # visible (key tile, query tile) pairs
+        cost[name] = {"atomic_bytes_after_lds_reduction": steps * 32768.0,
+                      "atomics_alone_ms": steps * 32768.0 / rate * 1e3,
+                      "atomics_alone_unreduced_ms": steps * 4 * 32768.0 / rate * 1e3}
+    print(json.dumps({"metric": "fp32 atomic-add rate in the dQ pattern of a fused backward", "unit": "TB/s of operand bytes",
+                      "rows": rows, "fused_backward_dq_cost": cost}), flush=True)
+
+
 def mfma_ceiling(torch, mb, iters=30000):
     """The MFMA-only rate this chip sustains, measured live: 256 workgroups x 8 waves issue nothing
     but bf16 32x32x16 MFMAs on (a) zeros and (b) N(0,1) operands.  The published peak assumes the
     nominal clock; under the power limit the clock, and with it the attainable rate, depends on the
     operand bits, so the attention kernels (N(0,1) inputs) are bounded by (b), not by the peak."""
     import ctypes
-    from paper_2407_12117_amd import build as memo_build
-    if not os.path.exists(memo_build.BENCH_AIDS_LIB):
-        memo_build.build_bench_aids()
-    aids = ctypes.CDLL(memo_build.BENCH_AIDS_LIB)
+    aids = bench_aids()
     aids.memo_bench_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_void_p]
     aids.memo_bench_probe_mfma.restype = ctypes.c_int

@@ -67,7 +67,8 @@ typedef struct {
     float scale;                /* the 1/sqrt(d) of the formula, passed explicitly */
     int64_t stride_b, stride_s, stride_h;
     int32_t causal;             /* must be 1: mask is inclusive, key j visible to query i iff j <= i */
-    uint32_t flags;             /* reserved, must be 0 */
+    uint32_t flags;             /* bit 0: bit-reproducible dq requested (always the case: the backward
+                                   uses no atomics, so the bit changes nothing); other bits must be 0 */
 } memo_attn_desc;
 
 /*

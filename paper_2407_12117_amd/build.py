@@ -7,8 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmemo.so")
-# measurement aids of bench.py (an MFMA-only probe): a library of their own, not part of libmemo
-BENCH_AIDS_SRC = os.path.join(HERE, "bench_aids", "probe_mfma.hip")
+# measurement aids of bench.py (an MFMA-only probe, an atomic-add probe): a library of their own, not part of libmemo
+BENCH_AIDS_SRC = [os.path.join(HERE, "bench_aids", "probe_mfma.hip"), os.path.join(HERE, "bench_aids", "atomic_add.hip")]
 BENCH_AIDS_LIB = os.path.join(HERE, "bench_aids", "libmemo_bench_aids.so")
 # source -> extra flags.  Every file keeps IEEE NaN semantics: a NaN or Inf in an input must reach
 # the outputs that depend on it (a training loop detects divergence that way).
@@ -18,6 +18,7 @@ SOURCES = {
     "memo_dsa.cpp": [],
     "attn_f32.hip": [],
     "attn_bf16.hip": [],
+    "attn_bwd_bf16.hip": [],
     "attn_bwd_static.hip": [],
     "recompute_bf16.hip": [],
 }
@@ -52,7 +53,7 @@ def build(verbose=False, extra=()):
 
 def build_bench_aids(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    _run([hipcc] + FLAGS + ["-shared", BENCH_AIDS_SRC, "-o", BENCH_AIDS_LIB], verbose)
+    _run([hipcc] + FLAGS + ["-shared"] + BENCH_AIDS_SRC + ["-o", BENCH_AIDS_LIB], verbose)
     return BENCH_AIDS_LIB
 
 

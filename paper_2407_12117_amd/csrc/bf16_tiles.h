@@ -30,7 +30,22 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Chunk swizzles of the 64-row x 256-byte LDS tile: the sixteen 16-byte chunks of row r are
+// stored at chunk position c ^ f(r), f of period 16 in r.  SwzA serves the 32x32x16 kernels
+// (lane 32*half + l32 reading chunk 2*kc + half of row l32; 32 lanes reading 4 rows x 64 bytes
+// transposed).  SwzB serves the 16x16x32 kernels (lane 16*g4 + l16 reading chunk 4*ks + g4 of row
+// l16; 16-lane groups reading rows 4*g4 .. 4*g4+3 x 32 bytes transposed).  Which lanes the LDS
+// serves in one cycle, and so which f are free of bank conflicts for a pattern, was found by
+// measurement (SQ_LDS_BANK_CONFLICT and read throughput over all 20160 invertible bit-linear f):
+// SwzA conflicts two-way on both patterns of the 16x16x32 kernels; SwzB is free on both.
+struct SwzA { static __device__ __forceinline__ int f(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); } };
+struct SwzB { static __device__ __forceinline__ int f(int r) { return ((((r & 7) << 1) | ((r >> 3) & 1)) ^ (r & 8)) & 15; } };
+__device__ __forceinline__ int swz(int r) { return SwzA::f(r); }
 
 // ---- per-lane LDS addressing ---------------------------------------------------------
 struct LaneAddr {
@@ -75,6 +90,48 @@ __device__ __forceinline__ LdsAddr make_lds_addr(const LDS_AS unsigned char *bas
     return ad;
 }
 
+// Per-lane LDS addresses of the 16x16x32 kernels (SwzB tiles), lane = 16*g4 + l16:
+//   row16[ks]  row-major operand: row l16 of a 16-row block, chunk 4*ks + g4 (k = 32*ks + 8*g4 ..)
+//   tr16[ct]   transposed operand of the 16 columns 16*ct ..: this lane's address in the
+//              ds_read_b64_tr_b16 of rows 4*g4 .. 4*g4+3 (lane i16 of a group supplies row i16/4,
+//              columns 4*(i16%4) .. and receives column i16); + 16 rows = + 4096 bytes
+struct LdsAddr16 { uint32_t row16[4]; uint32_t tr16[8]; };
+__device__ __forceinline__ LdsAddr16 make_lds_addr16(const LDS_AS unsigned char *base, int lane)
+{
+    LdsAddr16 ad;
+    const uint32_t b = (uint32_t)(uintptr_t)base;
+    const int l16 = lane & 15, g4 = lane >> 4;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ad.row16[ks] = b + (uint32_t)(l16 * 256 + (((4 * ks + g4) ^ SwzB::f(l16)) << 4));
+    const int row = 4 * g4 + (l16 >> 2);
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct)
+        ad.tr16[ct] = b + (uint32_t)(row * 256 + (((2 * ct + ((l16 & 3) >> 1)) ^ SwzB::f(row)) << 4) + 8 * (l16 & 1));
+    return ad;
+}
+
+// 8 fp32 (two accumulator quartets) -> 8 bf16
+__device__ __forceinline__ bf16x8 pack44(const f32x4 &lo, const f32x4 &hi)
+{
+    bf16x8 out;
+    f32x2 t0 = {lo[0], lo[1]}, t1 = {lo[2], lo[3]}, t2 = {hi[0], hi[1]}, t3 = {hi[2], hi[3]};
+    bf16x2 r0 = __builtin_convertvector(t0, bf16x2), r1 = __builtin_convertvector(t1, bf16x2);
+    bf16x2 r2 = __builtin_convertvector(t2, bf16x2), r3 = __builtin_convertvector(t3, bf16x2);
+    out[0] = r0[0]; out[1] = r0[1]; out[2] = r1[0]; out[3] = r1[1];
+    out[4] = r2[0]; out[5] = r2[1]; out[6] = r3[0]; out[7] = r3[1];
+    return out;
+}
+
+// 4 fp32 -> 4 bf16, stored as 8 bytes
+__device__ __forceinline__ void store4(__bf16 *dst, const f32x4 &x, float mul)
+{
+    f32x2 a = {x[0] * mul, x[1] * mul}, b = {x[2] * mul, x[3] * mul};
+    u32x2 w;
+    w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
+    w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2));
+    *reinterpret_cast<u32x2 *>(dst) = w;
+}
+
 // 8 fp32 -> 8 bf16 (round to nearest even)
 __device__ __forceinline__ bf16x8 pack8(const f32x16 &x, int first)
 {
@@ -107,10 +164,12 @@ __device__ __forceinline__ void store_acc_T(__bf16 *out_row, const f32x16 (&acc)
         }
 }
 
-// Workgroup id -> (tile, head, batch).  Consecutive ids, which the dispatcher deals
-// round-robin to the 8 XCDs, differ in the head, so with 1, 2, 4 or 8 heads every XCD's
-// L2 streams one head's tensors.  `reverse` issues the highest tile index first.
+// Workgroup id -> (tile, head, batch).  The dispatcher deals consecutive workgroup ids round-robin
+// to the 8 XCDs, each of which has its own L2.
 struct TileId { int64_t tile; int h, b; };
+
+// Interleaved order (dK/dV kernel): consecutive ids differ in the head, so with 1, 2, 4 or 8 heads
+// every XCD's L2 streams one head's tensors; tile 0 (the heaviest) first.
 __device__ __forceinline__ TileId decode_block(const AttnArgs &a, int64_t ntiles, bool reverse)
 {
     const int64_t hb = (int64_t)a.H * a.B;
@@ -119,6 +178,37 @@ __device__ __forceinline__ TileId decode_block(const AttnArgs &a, int64_t ntiles
     const int64_t ord = id / hb;
     t.tile = reverse ? ntiles - 1 - ord : ord;
     const int rem = (int)(id % hb);
+    t.h = rem % a.H;
+    t.b = rem / a.H;
+    return t;
+}
+
+// Chunked order (forward and dQ kernels, where every workgroup of a head streams K/V from row 0):
+// work is handed out in chunks of kChunk = 32 consecutive query tiles of one head (an XCD has 32
+// compute units and these kernels run one workgroup per unit).  Chunks are numbered heaviest first,
+// round-robin over the heads, and dealt to the XCDs in rounds of 8 whose direction alternates (so
+// that no XCD collects the heavy end of every round).  The workgroups resident on an XCD then start
+// together on tiles of nearly equal length and walk the same K/V rows at the same time, which is
+// what keeps those rows in that XCD's L2: HBM reads fall by a third (forward) to two thirds (dQ)
+// against the interleaved order.  tile = -1: an id past the end, nothing to do.
+constexpr int kXcds = 8, kChunk = 32;
+
+__host__ __device__ inline int64_t chunked_grid(int64_t ntiles, int64_t heads)
+{
+    const int64_t chunks = (ntiles + kChunk - 1) / kChunk * heads;
+    return (chunks + kXcds - 1) / kXcds * kXcds * kChunk;
+}
+
+__device__ __forceinline__ TileId decode_block_chunked(const AttnArgs &a, int64_t ntiles)
+{
+    const int64_t hb = (int64_t)a.H * a.B;
+    const int64_t id = blockIdx.x;
+    const int64_t xcd = id % kXcds, slot = id / kXcds, round = slot / kChunk;
+    const int64_t chunk = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
+    const int64_t ord = (chunk / hb) * kChunk + slot % kChunk;   // position in the head's heavy-to-light order
+    const int rem = (int)(chunk % hb);
+    TileId t;
+    t.tile = ord < ntiles ? ntiles - 1 - ord : -1;               // the highest query tile is the heaviest
     t.h = rem % a.H;
     t.b = rem / a.H;
     return t;
@@ -137,7 +227,7 @@ struct TileStream {
     const char *p[16 / NW];
 };
 
-template <int NW>
+template <int NW, typename SW = SwzA>
 __device__ __forceinline__ TileStream<NW> make_tile_stream(const __bf16 *src, int64_t ss, int64_t r0,
                                                            int wave, int lane)
 {
@@ -145,7 +235,7 @@ __device__ __forceinline__ TileStream<NW> make_tile_stream(const __bf16 *src, in
 #pragma unroll
     for (int n = 0; n < TileStream<NW>::kInstr; ++n) {
         const int row = 4 * (TileStream<NW>::kInstr * wave + n) + (lane >> 4);
-        const int chunk = (lane & 15) ^ swz(row);
+        const int chunk = (lane & 15) ^ SW::f(row);
         f.p[n] = reinterpret_cast<const char *>(src + (r0 + row) * ss + chunk * 8);
     }
     return f;
@@ -154,7 +244,7 @@ __device__ __forceinline__ TileStream<NW> make_tile_stream(const __bf16 *src, in
 // Queues the fill of the 64-row tile the stream points at (rows r0..r0+63 of the head view
 // `src`) and steps the stream to the next tile.  A tile that reaches past row S-1 takes the
 // slow path: rows past S re-read row S-1 (finite values; every consumer masks them).
-template <int NW>
+template <int NW, typename SW = SwzA>
 __device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, TileStream<NW> &f,
                                                 const __bf16 *src, int64_t ss, int64_t r0, int64_t S,
                                                 int wave, int lane)
@@ -169,7 +259,7 @@ __device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, Tile
 #pragma unroll
         for (int n = 0; n < NI; ++n) {
             const int row = 4 * (NI * wave + n) + (lane >> 4);
-            const int chunk = (lane & 15) ^ swz(row);
+            const int chunk = (lane & 15) ^ SW::f(row);
             int64_t rg = r0 + row;
             rg = rg < S ? rg : S - 1;
             __builtin_amdgcn_global_load_lds((const GLB_AS void *)(src + rg * ss + chunk * 8),
@@ -190,14 +280,14 @@ struct TileOffsets {
     uint32_t off[16 / NW];
 };
 
-template <int NW>
+template <int NW, typename SW = SwzA>
 __device__ __forceinline__ TileOffsets<NW> make_tile_offsets(int64_t ss, int wave, int lane)
 {
     TileOffsets<NW> f;
 #pragma unroll
     for (int n = 0; n < TileOffsets<NW>::kInstr; ++n) {
         const int row = 4 * (TileOffsets<NW>::kInstr * wave + n) + (lane >> 4);
-        const int chunk = (lane & 15) ^ swz(row);
+        const int chunk = (lane & 15) ^ SW::f(row);
         f.off[n] = (uint32_t)(row * ss * 2 + chunk * 16);
     }
     return f;
@@ -213,7 +303,7 @@ __device__ __forceinline__ void fill_full_tile_part(LDS_AS unsigned char *tile, 
 }
 
 // the ragged last tile: rows past S re-read row S-1 (finite values; every consumer masks them)
-template <int NW>
+template <int NW, typename SW = SwzA>
 __device__ __forceinline__ void fill_ragged_tile(LDS_AS unsigned char *tile, const __bf16 *src, int64_t ss,
                                                  int64_t r0, int64_t S, int wave, int lane)
 {
@@ -221,7 +311,7 @@ __device__ __forceinline__ void fill_ragged_tile(LDS_AS unsigned char *tile, con
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
         const int row = 4 * (NI * wave + n) + (lane >> 4);
-        const int chunk = (lane & 15) ^ swz(row);
+        const int chunk = (lane & 15) ^ SW::f(row);
         int64_t rg = r0 + row;
         rg = rg < S ? rg : S - 1;
         __builtin_amdgcn_global_load_lds((const GLB_AS void *)(src + rg * ss + chunk * 8),
@@ -265,6 +355,15 @@ __device__ __forceinline__ void lds_issue_tr(TrSlot &dst, uint32_t addr_lo, uint
     static_assert(OFF >= 0 && OFF < 65536, "LDS immediate offset");
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst.lo) : "v"(addr_lo), "n"(OFF) : "memory");
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst.hi) : "v"(addr_hi), "n"(OFF) : "memory");
+}
+
+// the two halves from one address register: rows +0 and +16 of a 32-row chunk (16x16x32 kernels)
+template <int OFF>
+__device__ __forceinline__ void lds_issue_tr_pair(TrSlot &dst, uint32_t addr)
+{
+    static_assert(OFF >= 0 && OFF + 4096 < 65536, "LDS immediate offset");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst.lo) : "v"(addr), "n"(OFF) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst.hi) : "v"(addr), "n"(OFF + 4096) : "memory");
 }
 
 template <int N>

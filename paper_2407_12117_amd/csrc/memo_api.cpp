@@ -18,7 +18,8 @@ memo_status check_desc(const memo_attn_desc *d, memo::AttnArgs *out)
     if (d->B <= 0 || d->H <= 0 || d->S <= 0 || d->d <= 0) return MEMO_ERR_INVALID_ARG;
     if (d->B > 65535 || d->H > 65535) return MEMO_ERR_INVALID_ARG;
     if (!(d->scale > 0.f) || !std::isfinite(d->scale)) return MEMO_ERR_INVALID_ARG;
-    if (d->causal != 1 || d->flags != 0) return MEMO_ERR_UNSUPPORTED;
+    // flags bit 0 asks for bit-reproducible gradients: every path here is, so it is accepted and changes nothing
+    if (d->causal != 1 || (d->flags & ~1u) != 0) return MEMO_ERR_UNSUPPORTED;
     if (d->dtype != MEMO_F32 && d->dtype != MEMO_BF16) return MEMO_ERR_UNSUPPORTED;
     if (d->dtype == MEMO_BF16 && d->d != 128) return MEMO_ERR_UNSUPPORTED;
     if (d->dtype == MEMO_F32 && d->d != 64 && d->d != 128) return MEMO_ERR_UNSUPPORTED;
@@ -27,8 +28,13 @@ memo_status check_desc(const memo_attn_desc *d, memo::AttnArgs *out)
     if (d->stride_b % vec || d->stride_s % vec || d->stride_h % vec) return MEMO_ERR_UNSUPPORTED;
     // the tile index arithmetic is 64-bit; the row count per launch must fit the grid
     if (d->S > ((int64_t)1 << 31) - 1024) return MEMO_ERR_UNSUPPORTED;
-    // one workgroup per 128-key tile (dK/dV kernel; the other bf16 kernels launch half as many)
-    if (d->dtype == MEMO_BF16 && ((d->S + 127) / 128) * d->H * d->B > 0x7fffffffLL) return MEMO_ERR_UNSUPPORTED;
+    // one workgroup per 128-key tile in the dK/dV kernel; the forward and dQ kernels launch one per
+    // 256 queries, in chunks of 32 tiles per head rounded up to a multiple of 8 chunks
+    if (d->dtype == MEMO_BF16) {
+        const int64_t hb = (int64_t)d->H * d->B;
+        if ((d->S + 127) / 128 * hb > 0x7fffffffLL) return MEMO_ERR_UNSUPPORTED;
+        if ((((d->S + 255) / 256 + 31) / 32 * hb + 7) / 8 * 256 > 0x7fffffffLL) return MEMO_ERR_UNSUPPORTED;
+    }
     // the bf16 tile fills address 64 rows with 32-bit per-lane byte offsets
     if (d->dtype == MEMO_BF16 && d->stride_s > ((int64_t)1 << 24)) return MEMO_ERR_UNSUPPORTED;
     std::memset(out, 0, sizeof(*out));

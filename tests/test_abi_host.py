@@ -76,7 +76,7 @@ def _desc(**kw):
     (dict(scale=float("nan")), mb.MEMO_ERR_INVALID_ARG),
     (dict(scale=-1.0), mb.MEMO_ERR_INVALID_ARG),
     (dict(causal=0), mb.MEMO_ERR_UNSUPPORTED),
-    (dict(flags=1), mb.MEMO_ERR_UNSUPPORTED),
+    (dict(flags=2), mb.MEMO_ERR_UNSUPPORTED),           # only bit 0 (deterministic dQ) is defined
     (dict(d=64), mb.MEMO_ERR_UNSUPPORTED),            # bf16 path is built for d = 128
     (dict(d=96, dtype=mb.MEMO_F32), mb.MEMO_ERR_UNSUPPORTED),
     (dict(dtype=7), mb.MEMO_ERR_UNSUPPORTED),
@@ -91,6 +91,12 @@ def test_attention_rejects_bad_descriptors_before_any_launch(kw, status):
     fake = ctypes.c_void_p(4096)
     assert mb.lib().memo_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, None) == status
     assert mb.lib().memo_attn_bwd_workspace_bytes(ctypes.byref(d)) == 0
+
+
+def test_deterministic_flag_is_accepted():
+    # bit 0 asks for bit-reproducible dQ; the backward has no atomics, so the bit is accepted as a no-op
+    assert mb.lib().memo_attn_bwd_workspace_bytes(ctypes.byref(_desc(flags=1))) == \
+        mb.lib().memo_attn_bwd_workspace_bytes(ctypes.byref(_desc(flags=0))) > 0
 
 
 def test_attention_rejects_null_and_misaligned_pointers():
