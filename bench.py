@@ -131,7 +131,10 @@ def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, 
         f0.record(compute)
         mb.memo_attn_fwd(q, k, v, scale, o=o, lse=lse)
         f1.record(compute)
-        # backward of the layer: prefetch the swapped tokens while attention backward runs
+        # backward of the layer: prefetch the swapped tokens while attention backward runs (the
+        # copy starts once the tokens are on the host AND the forward has ended, as in the
+        # schedule of Section 4.1 where a layer's swap-in runs beside a later layer's backward)
+        prefetch.wait_event(f1)
         mb.memo_swap_in(act_back, alpha, host, prefetch, wait_event=offloaded, done_event=fetched)
         mb.memo_attn_bwd(q, k, v, o, lse, g, scale, dq=dq, dk=dk, dv=dv, workspace=ws, stage_events=stages)
         compute.wait_event(fetched)                      # the consumer of the activation waits here

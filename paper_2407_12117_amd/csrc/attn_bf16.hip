@@ -49,20 +49,32 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
     const LaneAddr la = make_lane_addr(lane);
     const int64_t nqt = (a.S + kFwdBq - 1) / kFwdBq;
-    const TileId t = decode_block_chunked(a, nqt);    // heaviest query tiles first
-    if (t.tile < 0) return;
-    const int64_t row0 = t.tile * kFwdBq, i0w = row0 + 32 * wave, i = i0w + l32;
+    const PairId t = decode_block_folded(a, nqt);
+    if (t.first < 0) return;
     const int64_t base = (int64_t)t.b * a.sb + (int64_t)t.h * a.sh;
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *k = static_cast<const __bf16 *>(a.k) + base;
     const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
-    TileStream<kFwdWaves> ks = make_tile_stream<kFwdWaves>(k, a.ss, 0, wave, lane);
-    TileStream<kFwdWaves> vs = make_tile_stream<kFwdWaves>(v, a.ss, 0, wave, lane);
+    const float c = a.scale * kLog2e;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const LdsAddr ad = make_lds_addr(lds, la);
+    const uint32_t (&row_addr)[8] = ad.row;
+    const uint32_t (&tr_addr)[4][2] = ad.tr;
 
+    // the heavy tile of the pair sweeps the keys upwards from row 0, the light one downwards to row 0
+    // (online softmax takes the key tiles in any order)
+    for (int pass = 0; pass < 2; ++pass) {
+    const int64_t tile = pass == 0 ? (t.second >= 0 ? t.second : t.first) : (t.second >= 0 ? t.first : -1);
+    if (tile < 0) break;
+    const int64_t row0 = tile * kFwdBq, i0w = row0 + 32 * wave, i = i0w + l32;
     const int64_t last_row = min(row0 + kFwdBq, a.S) - 1;
     const int ntiles = (int)(last_row / kBk) + 1;
-    fill_tile_async(lds, ks, k, a.ss, 0, a.S, wave, lane);
-    fill_tile_async(lds + kTileBytes, vs, v, a.ss, 0, a.S, wave, lane);
+    const int jfirst = pass ? ntiles - 1 : 0, jstep = pass ? -1 : 1;
+    if (pass) __syncthreads();    // every wave has left the first tile's last LDS buffer
+    TileStream<kFwdWaves> ks = make_tile_stream<kFwdWaves>(k, a.ss, (int64_t)jfirst * kBk, wave, lane);
+    TileStream<kFwdWaves> vs = make_tile_stream<kFwdWaves>(v, a.ss, (int64_t)jfirst * kBk, wave, lane);
+    fill_tile_async(lds, ks, k, a.ss, (int64_t)jfirst * kBk, a.S, wave, lane, jstep);
+    fill_tile_async(lds + kTileBytes, vs, v, a.ss, (int64_t)jfirst * kBk, a.S, wave, lane, jstep);
 
     // Q^T as B operand: lane = query row i, 8 head-dim values per 16-wide chunk
     bf16x8 qB[8];
@@ -79,13 +91,8 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
 #pragma unroll
         for (int e = 0; e < 16; ++e) accO[cb][e] = 0.f;
     float m = -INFINITY, mc = -INFINITY, lsum = 0.f;   // running max of raw dots (and times c), running sum
-    const float c = a.scale * kLog2e;
     const int wave_first_tile_masked = (int)((i0w + 31) / kBk) + 1;   // tiles >= this are fully masked
     const int wave_first_diag = (int)(i0w / kBk);                     // tiles >= this need the mask
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const LdsAddr ad = make_lds_addr(lds, la);
-    const uint32_t (&row_addr)[8] = ad.row;
-    const uint32_t (&tr_addr)[4][2] = ad.tr;
 
     // One key/value tile.  BUF is a compile-time buffer index, so every LDS address below is
     // a per-lane register plus an immediate offset.
@@ -95,9 +102,10 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
         constexpr int nOff = (BUF ^ 1) * 2 * kTileBytes;
         wait_fills();
         __syncthreads();          // tile jt is complete; nobody still reads the other buffer
-        if (jt + 1 < ntiles) {
-            fill_tile_async(lds + nOff, ks, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
-            fill_tile_async(lds + nOff + kTileBytes, vs, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
+        const int jn = jt + jstep;
+        if (jn >= 0 && jn < ntiles) {
+            fill_tile_async(lds + nOff, ks, k, a.ss, (int64_t)jn * kBk, a.S, wave, lane, jstep);
+            fill_tile_async(lds + nOff + kTileBytes, vs, v, a.ss, (int64_t)jn * kBk, a.S, wave, lane, jstep);
         }
         if (jt >= wave_first_tile_masked) return;     // every key of this tile is masked for this wave
 
@@ -175,9 +183,9 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
         });
     };
 
-    for (int jt = 0; jt < ntiles; jt += 2) {
-        tile_step(IntC<0>{}, jt);
-        if (jt + 1 < ntiles) tile_step(IntC<1>{}, jt + 1);
+    for (int n = 0; n < ntiles; n += 2) {
+        tile_step(IntC<0>{}, jfirst + jstep * n);
+        if (n + 1 < ntiles) tile_step(IntC<1>{}, jfirst + jstep * (n + 1));
     }
 
     const float ltot = add_across_halves(lsum);
@@ -187,6 +195,7 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
         if (half == 0)
             a.lse[((int64_t)t.b * a.H + t.h) * a.S + i] = (mc + __builtin_amdgcn_logf(ltot)) * kLn2;
     }
+    }   // pass
 }
 
 }  // namespace
@@ -194,7 +203,7 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
 hipError_t launch_attn_fwd_bf16(const AttnArgs &a, hipStream_t st)
 {
     const int64_t nqt = (a.S + kFwdBq - 1) / kFwdBq;
-    const int64_t blocks = chunked_grid(nqt, (int64_t)a.H * a.B);
+    const int64_t blocks = folded_grid(nqt, (int64_t)a.H * a.B);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     attn_fwd_bf16_kernel<<<dim3((unsigned)blocks), 64 * kFwdWaves, 0, st>>>(a);
     return hipGetLastError();

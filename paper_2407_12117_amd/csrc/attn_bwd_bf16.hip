@@ -49,22 +49,31 @@ __global__ __launch_bounds__(64 * kDqWaves) void attn_bwd_dq_bf16_kernel(AttnArg
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t nqt = (a.S + kDqBq - 1) / kDqBq;
-    const TileId t = decode_block_chunked(a, nqt);
-    if (t.tile < 0) return;
-    const int64_t row0 = t.tile * kDqBq, i0w = row0 + 32 * wave;
+    const PairId t = decode_block_folded(a, nqt);
+    if (t.first < 0) return;
     const int64_t base = (int64_t)t.b * a.sb + (int64_t)t.h * a.sh;
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *k = static_cast<const __bf16 *>(a.k) + base;
     const __bf16 *v = static_cast<const __bf16 *>(a.v) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
     const int64_t stat = ((int64_t)t.b * a.H + t.h) * a.S;
-    TileStream<kDqWaves> ks = make_tile_stream<kDqWaves, SwzB>(k, a.ss, 0, wave, lane);
-    TileStream<kDqWaves> vs = make_tile_stream<kDqWaves, SwzB>(v, a.ss, 0, wave, lane);
+    const LdsAddr16 ad = make_lds_addr16(lds, lane);
+    const float c = a.scale * kLog2e;
 
+    // the heavy tile of the pair sweeps the keys upwards from row 0, the light one downwards to row 0
+    for (int pass = 0; pass < 2; ++pass) {
+    const int64_t tile = pass == 0 ? (t.second >= 0 ? t.second : t.first) : (t.second >= 0 ? t.first : -1);
+    if (tile < 0) break;
+    const bool down = pass == 1;
+    const int64_t row0 = tile * kDqBq, i0w = row0 + 32 * wave;
     const int64_t last_row = min(row0 + kDqBq, a.S) - 1;
     const int ntiles = (int)(last_row / kBk) + 1;
-    fill_tile_async<kDqWaves, SwzB>(lds, ks, k, a.ss, 0, a.S, wave, lane);
-    fill_tile_async<kDqWaves, SwzB>(lds + kTileBytes, vs, v, a.ss, 0, a.S, wave, lane);
+    const int jfirst = down ? ntiles - 1 : 0, jstep = down ? -1 : 1;
+    if (pass) __syncthreads();    // every wave has left the first tile's last LDS buffer
+    TileStream<kDqWaves> ks = make_tile_stream<kDqWaves, SwzB>(k, a.ss, (int64_t)jfirst * kBk, wave, lane);
+    TileStream<kDqWaves> vs = make_tile_stream<kDqWaves, SwzB>(v, a.ss, (int64_t)jfirst * kBk, wave, lane);
+    fill_tile_async<kDqWaves, SwzB>(lds, ks, k, a.ss, (int64_t)jfirst * kBk, a.S, wave, lane, jstep);
+    fill_tile_async<kDqWaves, SwzB>(lds + kTileBytes, vs, v, a.ss, (int64_t)jfirst * kBk, a.S, wave, lane, jstep);
 
     // Q^T and dO^T as B operands: lane = query 16*qt + l16, 8 head-dim values per 32-wide k step
     bf16x8 qB[2][4], gB[2][4];
@@ -84,8 +93,6 @@ __global__ __launch_bounds__(64 * kDqWaves) void attn_bwd_dq_bf16_kernel(AttnArg
         const float nd = -a.delta[stat + iq[qt]];
         neg_d[qt] = f32x4{nd, nd, nd, nd};
     }
-    const float c = a.scale * kLog2e;
-
     f32x4 accQ[8][2];             // dQ^T: [head-dim block of 16][query block]; lane = query, rows = head dim
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
@@ -93,7 +100,6 @@ __global__ __launch_bounds__(64 * kDqWaves) void attn_bwd_dq_bf16_kernel(AttnArg
         for (int qt = 0; qt < 2; ++qt) accQ[dt][qt] = kZero4;
     const int wave_first_tile_masked = (int)((i0w + 31) / kBk) + 1;   // tiles >= this are fully masked
     const int wave_first_diag = (int)(i0w / kBk);                     // tiles >= this need the mask
-    const LdsAddr16 ad = make_lds_addr16(lds, lane);
 
     auto tile_step = [&](auto bufc, int jt) {
         constexpr int BUF = decltype(bufc)::value;
@@ -101,9 +107,10 @@ __global__ __launch_bounds__(64 * kDqWaves) void attn_bwd_dq_bf16_kernel(AttnArg
         constexpr int nOff = (BUF ^ 1) * 2 * kTileBytes;
         wait_fills();
         __syncthreads();          // tile jt is complete; nobody still reads the other buffer
-        if (jt + 1 < ntiles) {
-            fill_tile_async<kDqWaves, SwzB>(lds + nOff, ks, k, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
-            fill_tile_async<kDqWaves, SwzB>(lds + nOff + kTileBytes, vs, v, a.ss, (int64_t)(jt + 1) * kBk, a.S, wave, lane);
+        const int jn = jt + jstep;
+        if (jn >= 0 && jn < ntiles) {
+            fill_tile_async<kDqWaves, SwzB>(lds + nOff, ks, k, a.ss, (int64_t)jn * kBk, a.S, wave, lane, jstep);
+            fill_tile_async<kDqWaves, SwzB>(lds + nOff + kTileBytes, vs, v, a.ss, (int64_t)jn * kBk, a.S, wave, lane, jstep);
         }
         if (jt >= wave_first_tile_masked) return;
         const bool diag = jt >= wave_first_diag;
@@ -166,9 +173,9 @@ __global__ __launch_bounds__(64 * kDqWaves) void attn_bwd_dq_bf16_kernel(AttnArg
             });
         });
     };
-    for (int jt = 0; jt < ntiles; jt += 2) {
-        tile_step(IntC<0>{}, jt);
-        if (jt + 1 < ntiles) tile_step(IntC<1>{}, jt + 1);
+    for (int n = 0; n < ntiles; n += 2) {
+        tile_step(IntC<0>{}, jfirst + jstep * n);
+        if (n + 1 < ntiles) tile_step(IntC<1>{}, jfirst + jstep * (n + 1));
     }
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
@@ -179,6 +186,7 @@ __global__ __launch_bounds__(64 * kDqWaves) void attn_bwd_dq_bf16_kernel(AttnArg
             for (int dt = 0; dt < 8; ++dt) store4(dq + 16 * dt, accQ[dt][qt], a.scale);
         }
     }
+    }   // pass
 }
 
 
@@ -431,7 +439,7 @@ hipError_t launch_attn_bwd_bf16(const AttnArgs &a, hipStream_t st)
 {
     const int64_t hb = (int64_t)a.H * a.B;
     const int64_t nkt = (a.S + kBwdBk - 1) / kBwdBk, nqt = (a.S + kDqBq - 1) / kDqBq;
-    const int64_t dq_blocks = chunked_grid(nqt, hb);
+    const int64_t dq_blocks = folded_grid(nqt, hb);
     if (nkt * hb > 0x7fffffffLL || dq_blocks > 0x7fffffffLL) return hipErrorInvalidValue;   // the front end checks too
     hipError_t e = record_stage(a, 0, st);
     if (e != hipSuccess) return e;

@@ -183,34 +183,40 @@ __device__ __forceinline__ TileId decode_block(const AttnArgs &a, int64_t ntiles
     return t;
 }
 
-// Chunked order (forward and dQ kernels, where every workgroup of a head streams K/V from row 0):
-// work is handed out in chunks of kChunk = 32 consecutive query tiles of one head (an XCD has 32
-// compute units and these kernels run one workgroup per unit).  Chunks are numbered heaviest first,
-// round-robin over the heads, and dealt to the XCDs in rounds of 8 whose direction alternates (so
-// that no XCD collects the heavy end of every round).  The workgroups resident on an XCD then start
-// together on tiles of nearly equal length and walk the same K/V rows at the same time, which is
-// what keeps those rows in that XCD's L2: HBM reads fall by a third (forward) to two thirds (dQ)
-// against the interleaved order.  tile = -1: an id past the end, nothing to do.
-constexpr int kXcds = 8, kChunk = 32;
+constexpr int kXcds = 8, kChunk = 32;   // XCDs per device; compute units (one workgroup each) per XCD
 
-__host__ __device__ inline int64_t chunked_grid(int64_t ntiles, int64_t heads)
+// Folded order (forward and dQ kernels, where every workgroup of a head streams K/V): a workgroup
+// works a PAIR of query tiles of one head, the p-th heaviest and the p-th lightest, so every
+// workgroup of a launch has the same length (ntiles + 1 tile units): a launch is a whole number of
+// equal rounds and no compute unit waits for a straggler, whatever S is.  Chunks of kChunk
+// consecutive pairs go to one XCD (the dispatcher deals consecutive workgroup ids round-robin to
+// the 8 XCDs; an XCD has 32 compute units and these kernels run one workgroup per unit), chunks of
+// one head to the 8 XCDs of a round.  The kernel sweeps the heavy tile's keys upwards from row 0
+// and the light tile's keys downwards to row 0: workgroup s of a chunk ends its first sweep 4*s
+// steps before workgroup 0 and begins its second one 4*s key tiles higher, so the lengths cancel
+// and the workgroups of an XCD read the same K/V rows at about the same time in both sweeps,
+// which is what lets that XCD's L2 serve most of those reads.
+struct PairId { int64_t first, second; int h, b; };   // first < 0: nothing to do; second < 0: one tile only
+
+__host__ __device__ inline int64_t folded_grid(int64_t ntiles, int64_t heads)
 {
-    const int64_t chunks = (ntiles + kChunk - 1) / kChunk * heads;
-    return (chunks + kXcds - 1) / kXcds * kXcds * kChunk;
+    const int64_t cph = ((ntiles + 1) / 2 + kChunk - 1) / kChunk;      // chunks per head
+    return (cph * heads + kXcds - 1) / kXcds * kXcds * kChunk;
 }
 
-__device__ __forceinline__ TileId decode_block_chunked(const AttnArgs &a, int64_t ntiles)
+__device__ __forceinline__ PairId decode_block_folded(const AttnArgs &a, int64_t ntiles)
 {
-    const int64_t hb = (int64_t)a.H * a.B;
+    const int64_t npairs = (ntiles + 1) / 2, cph = (npairs + kChunk - 1) / kChunk;
     const int64_t id = blockIdx.x;
-    const int64_t xcd = id % kXcds, slot = id / kXcds, round = slot / kChunk;
-    const int64_t chunk = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
-    const int64_t ord = (chunk / hb) * kChunk + slot % kChunk;   // position in the head's heavy-to-light order
-    const int rem = (int)(chunk % hb);
-    TileId t;
-    t.tile = ord < ntiles ? ntiles - 1 - ord : -1;               // the highest query tile is the heaviest
-    t.h = rem % a.H;
-    t.b = rem / a.H;
+    const int64_t chunk = id / (kXcds * kChunk) * kXcds + id % kXcds;  // round * 8 + xcd
+    const int64_t p = (chunk % cph) * kChunk + (id / kXcds) % kChunk;
+    const int64_t hbi = chunk / cph;
+    const bool live = hbi < (int64_t)a.H * a.B && p < npairs;
+    PairId t;
+    t.first = live ? p : -1;                                           // tile p and tile ntiles-1-p
+    t.second = (live && p != ntiles - 1 - p) ? ntiles - 1 - p : -1;
+    t.h = (int)(hbi % a.H);
+    t.b = (int)(hbi / a.H);
     return t;
 }
 
@@ -242,12 +248,12 @@ __device__ __forceinline__ TileStream<NW> make_tile_stream(const __bf16 *src, in
 }
 
 // Queues the fill of the 64-row tile the stream points at (rows r0..r0+63 of the head view
-// `src`) and steps the stream to the next tile.  A tile that reaches past row S-1 takes the
+// `src`) and steps the stream to the next tile (the previous one with dir = -1).  A tile that reaches past row S-1 takes the
 // slow path: rows past S re-read row S-1 (finite values; every consumer masks them).
 template <int NW, typename SW = SwzA>
 __device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, TileStream<NW> &f,
                                                 const __bf16 *src, int64_t ss, int64_t r0, int64_t S,
-                                                int wave, int lane)
+                                                int wave, int lane, int dir = 1)
 {
     constexpr int NI = TileStream<NW>::kInstr;
     if (__builtin_expect(r0 + 64 <= S, 1)) {
@@ -266,7 +272,7 @@ __device__ __forceinline__ void fill_tile_async(LDS_AS unsigned char *tile, Tile
                                              (LDS_AS void *)(tile + (NI * wave + n) * 1024), 16, 0, 0);
         }
     }
-    const int64_t step = 64 * ss * 2;
+    const int64_t step = dir * 64 * ss * 2;       // dir = -1: the stream walks towards row 0
 #pragma unroll
     for (int n = 0; n < NI; ++n) f.p[n] += step;
 }
