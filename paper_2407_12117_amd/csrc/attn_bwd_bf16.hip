@@ -191,17 +191,23 @@ __global__ __launch_bounds__(64 * kDqWaves) void attn_bwd_dq_bf16_kernel(AttnArg
 
 
 // ============================================================================ backward: dK, dV
-// Workgroup: 8 waves, 128 key rows whose K and V stay in LDS for the workgroup's lifetime;
-// queries streamed in tiles of 64 through the double-buffered ring (one barrier per tile).
-// Wave w owns the 32 x 32 block (queries 32*(w/4).., keys 32*(w%4)..) of every tile, as 2 x 2
-// blocks of 16, and runs all four contractions on it, so nothing passes between waves in the loop:
-//   S = Q K^T, dP = dO V^T - D      (both operands from LDS; lane = key, registers = queries)
-//   P = exp(S - LSE_i), dS = P dP
-//   dV^T += dO^T P,  dK^T += Q^T dS  (A = transposed LDS reads over the block's 32 queries,
+// Workgroup: 8 waves, 256 key rows whose K and V stay in LDS for the workgroup's lifetime (128 KB);
+// queries streamed in tiles of 32 through a double-buffered ring (Q and dO rows, 16 KB per stage,
+// one barrier per tile): LDS is full to the byte (160 KB).  The bytes streamed per (query, key) pair
+// are (Q + dO bytes per query) / (keys per workgroup): 256 resident keys halve the L2 -> LDS and the
+// HBM traffic of a 128-key workgroup for the same work per wave and step.
+// Wave w owns key rows 32*w .. 32*w+31 and all 32 queries of every tile, as 2 x 2 blocks of 16, and
+// runs all four contractions on its block, so nothing passes between waves:
+//   S = Q K^T - LSE/scale, dP = dO V^T - D   (both operands from LDS; lane = key, registers = queries;
+//                                             -LSE_i/scale and -D_i are the initial accumulators)
+//   P = exp2(scale log2e S), dS = P dP
+//   dV^T += dO^T P,  dK^T += Q^T dS  (A = transposed LDS reads over the tile's 32 queries,
 //                                     B = P / dS from registers; lane = key, rows = head dim)
-// Waves w and w+4 hold partial sums for the same keys over disjoint queries; they are added
-// through LDS once, after the loop (wave w finishes dV, wave w+4 finishes dK).  No atomics.
-constexpr int kBwdBk = 128, kBq = 64;
+// No atomics, no reduction across waves: every wave writes the dK and dV rows of its own keys.
+// The row statistics do not pass through LDS (there is no room left): see "Row statistics" below.
+constexpr int kBwdBk = 256, kBq = 32;
+constexpr int kStageBytes = 2 * kBq * 256;            // Q rows, then dO rows
+constexpr int kKvBlockBytes = 2 * 32 * 256;           // per wave: its 32 K rows, then its 32 V rows
 
 struct QuadSlot { bf16x8 a0, a1, b0, b1; };
 
@@ -214,110 +220,122 @@ __device__ __forceinline__ void lds_wait(QuadSlot &x)
 
 __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
 {
-    constexpr int kKsOff = 4 * kTileBytes, kVsOff = 6 * kTileBytes, kStatOff = 8 * kTileBytes;
-    // [buf][Q|dO] ring, K rows, V rows (128 x 256 B each), [buf][LSE*log2e | -D] rows
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[8 * kTileBytes + 1024];
+    constexpr int kKvOff = 2 * kStageBytes;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[kKvOff + 8 * kKvBlockBytes];   // 160 KB
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
-    LDS_AS float *Stat = (LDS_AS float *)(lds + kStatOff);      // [buf][2][64]
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kb = wave & 3, qh = wave >> 2;
     const int64_t nkt = (a.S + kBwdBk - 1) / kBwdBk;
     const TileId t = decode_block(a, nkt, false);     // key tile 0 sees every query: heaviest first
-    const int64_t col0 = t.tile * kBwdBk, j0w = col0 + 32 * kb;
+    const int64_t col0 = t.tile * kBwdBk, j0w = col0 + 32 * wave;
     const int64_t base = (int64_t)t.b * a.sb + (int64_t)t.h * a.sh;
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
-    const int64_t stat = ((int64_t)t.b * a.H + t.h) * a.S;
+    const float *lse = a.lse + ((int64_t)t.b * a.H + t.h) * a.S;
+    const float *dlt = a.delta + ((int64_t)t.b * a.H + t.h) * a.S;
 
     const int it0 = (int)(col0 / kBq);
     const int nit = (int)((a.S + kBq - 1) / kBq);
-    {   // resident K and V rows of this key tile (rows past S repeat row S-1, never stored)
+    {   // resident K and V rows (rows past S repeat row S-1, never stored): 32-row pieces, 8 waves x 4 rows
         const __bf16 *kp = static_cast<const __bf16 *>(a.k) + base;
         const __bf16 *vp = static_cast<const __bf16 *>(a.v) + base;
-        TileStream<8> ks = make_tile_stream<8, SwzB>(kp, a.ss, col0, wave, lane);
-        TileStream<8> vs = make_tile_stream<8, SwzB>(vp, a.ss, col0, wave, lane);
-        fill_tile_async<8, SwzB>(lds + kKsOff, ks, kp, a.ss, col0, a.S, wave, lane);
-        fill_tile_async<8, SwzB>(lds + kKsOff + kTileBytes, ks, kp, a.ss, col0 + 64, a.S, wave, lane);
-        fill_tile_async<8, SwzB>(lds + kVsOff, vs, vp, a.ss, col0, a.S, wave, lane);
-        fill_tile_async<8, SwzB>(lds + kVsOff + kTileBytes, vs, vp, a.ss, col0 + 64, a.S, wave, lane);
+#pragma unroll
+        for (int blk = 0; blk < 8; ++blk) {
+            fill_ragged_tile<16, SwzB>(lds + kKvOff + blk * kKvBlockBytes, kp, a.ss, col0 + 32 * blk, a.S, wave, lane);
+            fill_ragged_tile<16, SwzB>(lds + kKvOff + blk * kKvBlockBytes + 8192, vp, a.ss, col0 + 32 * blk, a.S, wave, lane);
+        }
     }
-    const TileOffsets<8> toff = make_tile_offsets<8, SwzB>(a.ss, wave, lane);
+    // a 32-row ring tile is one fill instruction per wave (rows 4*wave .. 4*wave+3)
+    const TileOffsets<16> toff = make_tile_offsets<16, SwzB>(a.ss, wave, lane);
     const int64_t tile_step_bytes = kBq * a.ss * 2;
     auto fill_tile = [&](LDS_AS unsigned char *dst, const __bf16 *src, int64_t r0) {
         if (r0 + kBq <= a.S) {
-            const char *tb = reinterpret_cast<const char *>(src) + (r0 / kBq) * tile_step_bytes;
-            fill_full_tile_part(dst, toff, 0, tb, wave);
-            fill_full_tile_part(dst, toff, 1, tb, wave);
+            fill_full_tile_part(dst, toff, 0, reinterpret_cast<const char *>(src) + (r0 / kBq) * tile_step_bytes, wave);
         } else {
-            fill_ragged_tile<8, SwzB>(dst, src, a.ss, r0, a.S, wave, lane);
+            int ln = lane;        // opaque copy: the addresses of this rare path are formed here, not kept in registers
+            asm volatile("" : "+v"(ln));
+            fill_ragged_tile<16, SwzB>(dst, src, a.ss, r0, a.S, wave, ln);
         }
     };
     fill_tile(lds, q, (int64_t)it0 * kBq);
-    fill_tile(lds + kTileBytes, g, (int64_t)it0 * kBq);
+    fill_tile(lds + kBq * 256, g, (int64_t)it0 * kBq);
 
-    const float c = a.scale * kLog2e;
+    const float c = a.scale * kLog2e, neg_inv_scale = -1.f / a.scale;
     f32x4 accV[8][2], accK[8][2];                     // dV^T, dK^T: [head-dim block][key block]; lane = key
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) accV[dt][kt] = accK[dt][kt] = kZero4;
 
-    // per-row statistics of a query tile: threads 0..63 LSE*log2e, threads 64..127 -D_i (negated so
-    // that it is the initial accumulator of dP).  Rows past S: LSE = +inf makes their P exactly zero.
-    // The value is loaded raw and only scaled when it is written to LDS a tile later, so that
-    // nothing waits for the load right after issuing it.
-    const float *stat_src = (tid < 64 ? a.lse : a.delta) + stat;
-    const float stat_pad = tid < 64 ? INFINITY : 0.f, stat_mul = tid < 64 ? kLog2e : -1.f;
-    auto load_stat = [&](int it) -> float {
-        const int64_t r = (int64_t)it * kBq + (tid & 63);
-        return (tid < 128 && r < a.S) ? stat_src[r] : stat_pad;
+    // Row statistics.  The accumulator registers of lane 16*g4 + l16 stand for queries 4*g4 .. 4*g4+3 of a
+    // 16-query block, so the lane needs -LSE_i/scale and -D_i of those four queries as the initial value
+    // of S and dP: sixteen values per step.  Fetching them as such (from global memory or through LDS)
+    // returns 64 bytes per lane and step to the registers, which costs the step 6 %.  Instead lane l
+    // loads ONE value per block and statistic, that of query 4*(l/16) + l%4, and a 4x4x1 fp32 MFMA
+    // (sixteen independent 4x4 outer products, block = l/4) spreads it: with B = the scaling constant in
+    // every lane, register r of lane l receives A of lane 4*(l/4) + r, which is query 4*(l/16) + r.
+    // The product is one fp32 multiplication, the same rounding as a v_mul.  Rows past S: LSE = +inf
+    // makes their P exactly zero.
+    const int stat_lane = 4 * g4 + (lane & 3);
+    struct RawStats { float l[2], d[2]; };
+    auto load_stats = [&](int it) {
+        RawStats r;
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            const int64_t row = (int64_t)it * kBq + 16 * qt + stat_lane;
+            r.l[qt] = row < a.S ? lse[row] : INFINITY;
+            r.d[qt] = row < a.S ? dlt[row] : 0.f;
+        }
+        return r;
     };
-    float sreg = load_stat(it0);
-    if (tid < 128) Stat[tid] = sreg * stat_mul;
+    f32x4 nl[2], nd[2];           // -LSE_i/scale and -D_i of the tile about to be worked
+    auto spread_stats = [&](const RawStats &r) {
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            nl[qt] = __builtin_amdgcn_mfma_f32_4x4x1f32(r.l[qt], neg_inv_scale, kZero4, 0, 0, 0);
+            nd[qt] = __builtin_amdgcn_mfma_f32_4x4x1f32(r.d[qt], -1.f, kZero4, 0, 0, 0);
+        }
+    };
+    RawStats raw = load_stats(it0);
 
     const LdsAddr16 ad = make_lds_addr16(lds, lane);
-    uint32_t q_row[4], kv_row[4], q_tr[8];            // this wave's query rows of the ring tiles, its key rows
+    uint32_t kv_row[4];                               // this wave's K rows; its V rows are 8192 bytes further
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        q_row[kk] = ad.row16[kk] + (uint32_t)(qh * 8192);
-        kv_row[kk] = ad.row16[kk] + (uint32_t)(kKsOff + kb * 8192);
-    }
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt) q_tr[dt] = ad.tr16[dt] + (uint32_t)(qh * 8192);
+    for (int kk = 0; kk < 4; ++kk) kv_row[kk] = ad.row16[kk] + (uint32_t)(kKvOff + wave * kKvBlockBytes);
+    const uint32_t (&q_row)[4] = ad.row16;            // query rows of ring stage 0 (Q part)
+    const uint32_t (&q_tr)[8] = ad.tr16;
 
     auto tile_step = [&](auto bufc, int it) {
         constexpr int BUF = decltype(bufc)::value;
-        constexpr int qOff = BUF * 2 * kTileBytes, gOff = qOff + kTileBytes;
-        constexpr int nOff = (BUF ^ 1) * 2 * kTileBytes;
-        const LDS_AS float *Ls = Stat + BUF * 128, *Ds = Ls + 64;
+        constexpr int qOff = BUF * kStageBytes, gOff = qOff + kBq * 256;
+        constexpr int nOff = (BUF ^ 1) * kStageBytes;
         wait_fills();
-        __syncthreads();          // tile `it` and its statistics are complete; the other buffers are free
+        __syncthreads();          // tile `it` is complete; the other stage is free
         const bool more = it + 1 < nit;
         const int64_t rn = (int64_t)(it + 1) * kBq;
-        if (more) sreg = load_stat(it + 1);
-        const int64_t i0 = (int64_t)it * kBq + 32 * qh;           // first query of this wave's block
+        const int64_t i0 = (int64_t)it * kBq;         // first query of the tile
+        const RawStats raw_now = raw;
+        if (more) raw = load_stats(it + 1);           // four registers, used a whole step from now
         const bool active = i0 + 31 >= j0w;           // else all 32 queries precede this wave's keys
-        // A full next tile is fetched by four fill instructions queued one at a time between the
+        // A full next tile is fetched by two fill instructions queued one at a time between the
         // MFMAs below; the ragged last tile (and a wave with nothing to compute) queues them here.
         const bool spread = more && active && rn + kBq <= a.S;
         if (more && !spread) {
             fill_tile(lds + nOff, q, rn);
-            fill_tile(lds + nOff + kTileBytes, g, rn);
+            fill_tile(lds + nOff + kBq * 256, g, rn);
         }
         const char *nq = reinterpret_cast<const char *>(q) + (int64_t)(it + 1) * tile_step_bytes;
         const char *ng = reinterpret_cast<const char *>(g) + (int64_t)(it + 1) * tile_step_bytes;
         auto fill_part = [&](auto pc) {
             constexpr int part = decltype(pc)::value;
             if (!spread) return;
-            fill_full_tile_part(lds + nOff + (part / 2) * kTileBytes, toff, part % 2, part < 2 ? nq : ng, wave);
+            fill_full_tile_part(lds + nOff + part * kBq * 256, toff, 0, part == 0 ? nq : ng, wave);
         };
         if (active) {
+            spread_stats(raw_now);
             const bool diag = i0 < j0w + 31;
-            f32x4 s[2][2], dp[2][2], neg_d[2];        // [query block][key block]; register r = query 16*qt + 4*g4 + r
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt) neg_d[qt] = *reinterpret_cast<const LDS_AS f32x4 *>(Ds + 32 * qh + 16 * qt + 4 * g4);
+            f32x4 s[2][2], dp[2][2];                  // [query block][key block]; register r = query 16*qt + 4*g4 + r
             {
                 // item n = (k step n/2, S or dP = n%2): the Q (dO) rows of both query blocks and the
                 // K (V) rows of both key blocks, four MFMAs
@@ -326,24 +344,25 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
                     constexpr int kk = decltype(n)::value / 2, which = decltype(n)::value % 2;
                     lds_issue_b128<(which ? gOff : qOff)>(slot.a0, q_row[kk]);
                     lds_issue_b128<(which ? gOff : qOff) + 4096>(slot.a1, q_row[kk]);
-                    lds_issue_b128<(which ? kVsOff - kKsOff : 0)>(slot.b0, kv_row[kk]);
-                    lds_issue_b128<(which ? kVsOff - kKsOff : 0) + 4096>(slot.b1, kv_row[kk]);
+                    lds_issue_b128<(which ? 8192 : 0)>(slot.b0, kv_row[kk]);
+                    lds_issue_b128<(which ? 8192 : 0) + 4096>(slot.b1, kv_row[kk]);
                 };
                 lds_pipeline_prologue<8, 1, 4>(ring, issue);
                 lds_pipeline_body<8, 1, 4>(ring, issue, [&](auto n, QuadSlot &slot) {
                     constexpr int kk = decltype(n)::value / 2, which = decltype(n)::value % 2;
                     if constexpr (which == 0) {
-                        s[0][0] = mfma16(slot.a0, slot.b0, kk == 0 ? kZero4 : s[0][0]);
-                        s[0][1] = mfma16(slot.a0, slot.b1, kk == 0 ? kZero4 : s[0][1]);
-                        s[1][0] = mfma16(slot.a1, slot.b0, kk == 0 ? kZero4 : s[1][0]);
-                        s[1][1] = mfma16(slot.a1, slot.b1, kk == 0 ? kZero4 : s[1][1]);
+                        s[0][0] = mfma16(slot.a0, slot.b0, kk == 0 ? nl[0] : s[0][0]);
+                        s[0][1] = mfma16(slot.a0, slot.b1, kk == 0 ? nl[0] : s[0][1]);
+                        s[1][0] = mfma16(slot.a1, slot.b0, kk == 0 ? nl[1] : s[1][0]);
+                        s[1][1] = mfma16(slot.a1, slot.b1, kk == 0 ? nl[1] : s[1][1]);
                     } else {
-                        dp[0][0] = mfma16(slot.a0, slot.b0, kk == 0 ? neg_d[0] : dp[0][0]);
-                        dp[0][1] = mfma16(slot.a0, slot.b1, kk == 0 ? neg_d[0] : dp[0][1]);
-                        dp[1][0] = mfma16(slot.a1, slot.b0, kk == 0 ? neg_d[1] : dp[1][0]);
-                        dp[1][1] = mfma16(slot.a1, slot.b1, kk == 0 ? neg_d[1] : dp[1][1]);
+                        dp[0][0] = mfma16(slot.a0, slot.b0, kk == 0 ? nd[0] : dp[0][0]);
+                        dp[0][1] = mfma16(slot.a0, slot.b1, kk == 0 ? nd[0] : dp[0][1]);
+                        dp[1][0] = mfma16(slot.a1, slot.b0, kk == 0 ? nd[1] : dp[1][0]);
+                        dp[1][1] = mfma16(slot.a1, slot.b1, kk == 0 ? nd[1] : dp[1][1]);
                     }
-                    if constexpr (decltype(n)::value % 2 == 1) fill_part(IntC<decltype(n)::value / 2>{});
+                    if constexpr (decltype(n)::value == 3) fill_part(IntC<0>{});
+                    if constexpr (decltype(n)::value == 7) fill_part(IntC<1>{});
                 });
             }
             // item n < 8: dV^T head-dim block n, A = dO^T; n >= 8: dK^T block n - 8, A = Q^T
@@ -359,7 +378,7 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
                 for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
                     for (int kt = 0; kt < 2; ++kt) {
-                        // query offset 16qt + 4g4 + r of the block is visible to key j iff it is >= j - i0
+                        // query offset 16qt + 4g4 + r of the tile is visible to key j iff it is >= j - i0
                         const int thr = (int)(j0w + 16 * kt + l16 - i0) - (16 * qt + 4 * g4);
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
@@ -367,17 +386,15 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
                     }
             }
 #pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-                const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4 *>(Ls + 32 * qh + 16 * qt + 4 * g4);
+            for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float p = __builtin_amdgcn_exp2f(fmaf(s[qt][kt][r], c, -l4[r]));
+                        const float p = __builtin_amdgcn_exp2f(s[qt][kt][r] * c);   // s already holds S - LSE_i/scale
                         s[qt][kt][r] = p;
-                        dp[qt][kt][r] = p * dp[qt][kt][r];          // dp already holds dP - D_i
+                        dp[qt][kt][r] = p * dp[qt][kt][r];                          // dp already holds dP - D_i
                     }
-            }
             bf16x8 pB[2], dsB[2];
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
@@ -393,39 +410,22 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
                 }
             });
         }
-        if (more && tid < 128) Stat[(BUF ^ 1) * 128 + tid] = sreg * stat_mul;
     };
     for (int it = it0; it < nit; it += 2) {
         tile_step(IntC<0>{}, it);
         if (it + 1 < nit) tile_step(IntC<1>{}, it + 1);
     }
 
-    // Add the two query halves: wave (kb, 0) hands its dK^T to wave (kb, 1) and takes that
-    // wave's dV^T, as register images (lane l reads what lane l of the partner wrote).
-    __syncthreads();              // every wave is done with the tiles
-    {
-        LDS_AS f32x4 *mine = (LDS_AS f32x4 *)lds + (size_t)wave * 1024 + lane;          // 16 KB per wave
-        LDS_AS f32x4 *theirs = (LDS_AS f32x4 *)lds + (size_t)(wave ^ 4) * 1024 + lane;
-        f32x4 (&give)[8][2] = qh == 0 ? accK : accV;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) mine[(dt * 2 + kt) * 64] = give[dt][kt];
-        __syncthreads();
-        f32x4 (&keep)[8][2] = qh == 0 ? accV : accK;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            const int64_t j = j0w + 16 * kt + l16;
+    for (int kt = 0; kt < 2; ++kt) {
+        const int64_t j = j0w + 16 * kt + l16;
+        if (j < a.S) {
+            __bf16 *dv = static_cast<__bf16 *>(a.dv) + base + j * a.ss + 4 * g4;
+            __bf16 *dk = static_cast<__bf16 *>(a.dk) + base + j * a.ss + 4 * g4;
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
-                const f32x4 x = theirs[(dt * 2 + kt) * 64];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) keep[dt][kt][r] += x[r];
-            }
-            if (j < a.S) {
-                __bf16 *out = static_cast<__bf16 *>(qh == 0 ? a.dv : a.dk) + base + j * a.ss + 4 * g4;
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) store4(out + 16 * dt, keep[dt][kt], qh == 0 ? 1.f : a.scale);
+                store4(dv + 16 * dt, accV[dt][kt], 1.f);
+                store4(dk + 16 * dt, accK[dt][kt], a.scale);
             }
         }
     }

@@ -1,6 +1,7 @@
 """GPU parity: the HIP attention path vs the fp64 oracle, element by element, through the
 C-ABI.  Sizes here are ones the dense oracle finishes in seconds; they span several tiles
-(128-row query tiles, 64/128-row key tiles) and ragged tails."""
+(256-row query tiles and 64-row key tiles in the forward and dQ kernels, 256-row key tiles and 32-row
+query tiles in the dK/dV kernel) and ragged tails."""
 import math
 
 import numpy as np
@@ -40,7 +41,7 @@ def test_fp32_ragged_and_small(oracle, B, S, H, d):
     _dense_case(oracle, B, S, H, d, "f32", 7 + S)
 
 
-@pytest.mark.parametrize("S", [1, 2, 31, 63, 64, 65, 127, 128, 129, 200, 255, 256, 257, 383, 385, 511, 513, 777])
+@pytest.mark.parametrize("S", [1, 2, 31, 32, 33, 63, 64, 65, 97, 127, 128, 129, 200, 255, 256, 257, 287, 289, 383, 385, 511, 513, 777])
 def test_bf16_small_and_ragged(oracle, S):
     _dense_case(oracle, 2, S, 2, 128, "bf16", 100 + S)
 
