@@ -51,7 +51,8 @@ typedef enum { MEMO_F32 = 0, MEMO_BF16 = 1 } memo_dtype;
  * S may be any positive length (ragged last tile is handled); causal must be 1.
  * Rows must be 16-byte aligned: base pointers 16-byte aligned and strides a
  * multiple of 8 (bf16) or 4 (fp32) elements.  MEMO_BF16: stride_s <= 2^24 elements and
- * ceil(S/256) * H * B < 2^31 (one workgroup per key tile); MEMO_ERR_UNSUPPORTED otherwise.
+ * about S * H * B < 2^40 (one workgroup per pair of 256-row tiles, in chunks of 32 pairs per head
+ * rounded up to 8 chunks, must fit a 2^31 grid); MEMO_ERR_UNSUPPORTED otherwise.
  * Non-finite inputs: the kernels keep IEEE semantics, so a NaN or an infinity in q, k, v or d_o
  * reaches every output element that depends on it: a NaN in key row j makes o, lse, dq of all
  * query rows i >= j non-finite and, through them, all of dk and dv of that head.  It may also

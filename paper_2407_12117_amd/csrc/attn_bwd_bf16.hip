@@ -227,28 +227,42 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t nkt = (a.S + kBwdBk - 1) / kBwdBk;
-    const TileId t = decode_block(a, nkt, false);     // key tile 0 sees every query: heaviest first
-    const int64_t col0 = t.tile * kBwdBk, j0w = col0 + 32 * wave;
+    const PairId t = decode_block_folded(a, nkt);     // key tile p (long) and key tile nkt-1-p (short)
+    if (t.first < 0) return;
     const int64_t base = (int64_t)t.b * a.sb + (int64_t)t.h * a.sh;
     const __bf16 *q = static_cast<const __bf16 *>(a.q) + base;
     const __bf16 *g = static_cast<const __bf16 *>(a.d_o) + base;
     const float *lse = a.lse + ((int64_t)t.b * a.H + t.h) * a.S;
     const float *dlt = a.delta + ((int64_t)t.b * a.H + t.h) * a.S;
-
-    const int it0 = (int)(col0 / kBq);
     const int nit = (int)((a.S + kBq - 1) / kBq);
+    const float c = a.scale * kLog2e, neg_inv_scale = -1.f / a.scale;
+    const TileOffsets<16> toff = make_tile_offsets<16, SwzB>(a.ss, wave, lane);   // a 32-row ring tile is one fill instruction per wave
+    const int64_t tile_step_bytes = kBq * a.ss * 2;
+    const LdsAddr16 ad = make_lds_addr16(lds, lane);
+
+    // The long tile walks the query tiles downwards from the last one to its diagonal, the short tile
+    // upwards from its diagonal to the last one (the sums take the query tiles in any order): the
+    // workgroups of a chunk, which share an XCD and its L2, then read the same Q/dO rows at about the
+    // same time in both sweeps (bf16_tiles.h, folded order).
+    for (int pass = 0; pass < 2; ++pass) {
+    const int64_t tile = pass == 0 ? t.first : t.second;
+    if (tile < 0) break;
+    const int dir = pass == 0 ? -1 : 1;
+    const int64_t col0 = tile * kBwdBk, j0w = col0 + 32 * wave;
+    const int it0 = (int)(col0 / kBq);                // the tile's first query tile (its diagonal)
+    const int it_first = dir > 0 ? it0 : nit - 1, nsteps = nit - it0;
+    if (pass) __syncthreads();    // every wave has left the first tile's K, V and ring
     {   // resident K and V rows (rows past S repeat row S-1, never stored): 32-row pieces, 8 waves x 4 rows
         const __bf16 *kp = static_cast<const __bf16 *>(a.k) + base;
         const __bf16 *vp = static_cast<const __bf16 *>(a.v) + base;
+        int ln = lane;            // opaque copy: these addresses are formed here, once per sweep, not kept in registers
+        asm volatile("" : "+v"(ln));
 #pragma unroll
         for (int blk = 0; blk < 8; ++blk) {
-            fill_ragged_tile<16, SwzB>(lds + kKvOff + blk * kKvBlockBytes, kp, a.ss, col0 + 32 * blk, a.S, wave, lane);
-            fill_ragged_tile<16, SwzB>(lds + kKvOff + blk * kKvBlockBytes + 8192, vp, a.ss, col0 + 32 * blk, a.S, wave, lane);
+            fill_ragged_tile<16, SwzB>(lds + kKvOff + blk * kKvBlockBytes, kp, a.ss, col0 + 32 * blk, a.S, wave, ln);
+            fill_ragged_tile<16, SwzB>(lds + kKvOff + blk * kKvBlockBytes + 8192, vp, a.ss, col0 + 32 * blk, a.S, wave, ln);
         }
     }
-    // a 32-row ring tile is one fill instruction per wave (rows 4*wave .. 4*wave+3)
-    const TileOffsets<16> toff = make_tile_offsets<16, SwzB>(a.ss, wave, lane);
-    const int64_t tile_step_bytes = kBq * a.ss * 2;
     auto fill_tile = [&](LDS_AS unsigned char *dst, const __bf16 *src, int64_t r0) {
         if (r0 + kBq <= a.S) {
             fill_full_tile_part(dst, toff, 0, reinterpret_cast<const char *>(src) + (r0 / kBq) * tile_step_bytes, wave);
@@ -258,10 +272,9 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
             fill_ragged_tile<16, SwzB>(dst, src, a.ss, r0, a.S, wave, ln);
         }
     };
-    fill_tile(lds, q, (int64_t)it0 * kBq);
-    fill_tile(lds + kBq * 256, g, (int64_t)it0 * kBq);
+    fill_tile(lds, q, (int64_t)it_first * kBq);
+    fill_tile(lds + kBq * 256, g, (int64_t)it_first * kBq);
 
-    const float c = a.scale * kLog2e, neg_inv_scale = -1.f / a.scale;
     f32x4 accV[8][2], accK[8][2];                     // dV^T, dK^T: [head-dim block][key block]; lane = key
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
@@ -297,26 +310,24 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
             nd[qt] = __builtin_amdgcn_mfma_f32_4x4x1f32(r.d[qt], -1.f, kZero4, 0, 0, 0);
         }
     };
-    RawStats raw = load_stats(it0);
+    RawStats raw = load_stats(it_first);
 
-    const LdsAddr16 ad = make_lds_addr16(lds, lane);
     uint32_t kv_row[4];                               // this wave's K rows; its V rows are 8192 bytes further
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) kv_row[kk] = ad.row16[kk] + (uint32_t)(kKvOff + wave * kKvBlockBytes);
     const uint32_t (&q_row)[4] = ad.row16;            // query rows of ring stage 0 (Q part)
     const uint32_t (&q_tr)[8] = ad.tr16;
 
-    auto tile_step = [&](auto bufc, int it) {
+    auto tile_step = [&](auto bufc, int it, bool more) {
         constexpr int BUF = decltype(bufc)::value;
         constexpr int qOff = BUF * kStageBytes, gOff = qOff + kBq * 256;
         constexpr int nOff = (BUF ^ 1) * kStageBytes;
         wait_fills();
         __syncthreads();          // tile `it` is complete; the other stage is free
-        const bool more = it + 1 < nit;
-        const int64_t rn = (int64_t)(it + 1) * kBq;
+        const int64_t rn = (int64_t)(it + dir) * kBq;   // first query of the next tile (if there is one)
         const int64_t i0 = (int64_t)it * kBq;         // first query of the tile
         const RawStats raw_now = raw;
-        if (more) raw = load_stats(it + 1);           // four registers, used a whole step from now
+        if (more) raw = load_stats(it + dir);         // four registers, used a whole step from now
         const bool active = i0 + 31 >= j0w;           // else all 32 queries precede this wave's keys
         // A full next tile is fetched by two fill instructions queued one at a time between the
         // MFMAs below; the ragged last tile (and a wave with nothing to compute) queues them here.
@@ -325,8 +336,8 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
             fill_tile(lds + nOff, q, rn);
             fill_tile(lds + nOff + kBq * 256, g, rn);
         }
-        const char *nq = reinterpret_cast<const char *>(q) + (int64_t)(it + 1) * tile_step_bytes;
-        const char *ng = reinterpret_cast<const char *>(g) + (int64_t)(it + 1) * tile_step_bytes;
+        const char *nq = reinterpret_cast<const char *>(q) + (int64_t)(it + dir) * tile_step_bytes;
+        const char *ng = reinterpret_cast<const char *>(g) + (int64_t)(it + dir) * tile_step_bytes;
         auto fill_part = [&](auto pc) {
             constexpr int part = decltype(pc)::value;
             if (!spread) return;
@@ -411,17 +422,19 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
             });
         }
     };
-    for (int it = it0; it < nit; it += 2) {
-        tile_step(IntC<0>{}, it);
-        if (it + 1 < nit) tile_step(IntC<1>{}, it + 1);
+    for (int n = 0; n < nsteps; n += 2) {
+        tile_step(IntC<0>{}, it_first + dir * n, n + 1 < nsteps);
+        if (n + 1 < nsteps) tile_step(IntC<1>{}, it_first + dir * (n + 1), n + 2 < nsteps);
     }
 
+    int g4e = g4;                 // opaque copy: the output addresses are formed here, once per sweep, not kept in registers
+    asm volatile("" : "+v"(g4e));
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
         const int64_t j = j0w + 16 * kt + l16;
         if (j < a.S) {
-            __bf16 *dv = static_cast<__bf16 *>(a.dv) + base + j * a.ss + 4 * g4;
-            __bf16 *dk = static_cast<__bf16 *>(a.dk) + base + j * a.ss + 4 * g4;
+            __bf16 *dv = static_cast<__bf16 *>(a.dv) + base + j * a.ss + 4 * g4e;
+            __bf16 *dk = static_cast<__bf16 *>(a.dk) + base + j * a.ss + 4 * g4e;
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
                 store4(dv + 16 * dt, accV[dt][kt], 1.f);
@@ -429,6 +442,7 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkdv_bf16_kernel(AttnArgs a)
             }
         }
     }
+    }   // pass
 }
 
 }  // namespace
@@ -440,12 +454,13 @@ hipError_t launch_attn_bwd_bf16(const AttnArgs &a, hipStream_t st)
     const int64_t hb = (int64_t)a.H * a.B;
     const int64_t nkt = (a.S + kBwdBk - 1) / kBwdBk, nqt = (a.S + kDqBq - 1) / kDqBq;
     const int64_t dq_blocks = folded_grid(nqt, hb);
-    if (nkt * hb > 0x7fffffffLL || dq_blocks > 0x7fffffffLL) return hipErrorInvalidValue;   // the front end checks too
+    const int64_t dkdv_blocks = folded_grid(nkt, hb);
+    if (dkdv_blocks > 0x7fffffffLL || dq_blocks > 0x7fffffffLL) return hipErrorInvalidValue;   // the front end checks too
     hipError_t e = record_stage(a, 0, st);
     if (e != hipSuccess) return e;
     if ((e = launch_attn_delta(a, true, st)) != hipSuccess) return e;
     if ((e = record_stage(a, 1, st)) != hipSuccess) return e;
-    attn_bwd_dkdv_bf16_kernel<<<dim3((unsigned)(nkt * hb)), 512, 0, st>>>(a);
+    attn_bwd_dkdv_bf16_kernel<<<dim3((unsigned)dkdv_blocks), 512, 0, st>>>(a);
     if ((e = record_stage(a, 2, st)) != hipSuccess) return e;
     attn_bwd_dq_bf16_kernel<<<dim3((unsigned)dq_blocks), 64 * kDqWaves, 0, st>>>(a);
     if ((e = record_stage(a, 3, st)) != hipSuccess) return e;

@@ -164,38 +164,24 @@ __device__ __forceinline__ void store_acc_T(__bf16 *out_row, const f32x16 (&acc)
         }
 }
 
-// Workgroup id -> (tile, head, batch).  The dispatcher deals consecutive workgroup ids round-robin
-// to the 8 XCDs, each of which has its own L2.
-struct TileId { int64_t tile; int h, b; };
-
-// Interleaved order (dK/dV kernel): consecutive ids differ in the head, so with 1, 2, 4 or 8 heads
-// every XCD's L2 streams one head's tensors; tile 0 (the heaviest) first.
-__device__ __forceinline__ TileId decode_block(const AttnArgs &a, int64_t ntiles, bool reverse)
-{
-    const int64_t hb = (int64_t)a.H * a.B;
-    const int64_t id = blockIdx.x;
-    TileId t;
-    const int64_t ord = id / hb;
-    t.tile = reverse ? ntiles - 1 - ord : ord;
-    const int rem = (int)(id % hb);
-    t.h = rem % a.H;
-    t.b = rem / a.H;
-    return t;
-}
-
 constexpr int kXcds = 8, kChunk = 32;   // XCDs per device; compute units (one workgroup each) per XCD
 
-// Folded order (forward and dQ kernels, where every workgroup of a head streams K/V): a workgroup
-// works a PAIR of query tiles of one head, the p-th heaviest and the p-th lightest, so every
-// workgroup of a launch has the same length (ntiles + 1 tile units): a launch is a whole number of
-// equal rounds and no compute unit waits for a straggler, whatever S is.  Chunks of kChunk
-// consecutive pairs go to one XCD (the dispatcher deals consecutive workgroup ids round-robin to
-// the 8 XCDs; an XCD has 32 compute units and these kernels run one workgroup per unit), chunks of
-// one head to the 8 XCDs of a round.  The kernel sweeps the heavy tile's keys upwards from row 0
-// and the light tile's keys downwards to row 0: workgroup s of a chunk ends its first sweep 4*s
-// steps before workgroup 0 and begins its second one 4*s key tiles higher, so the lengths cancel
-// and the workgroups of an XCD read the same K/V rows at about the same time in both sweeps,
-// which is what lets that XCD's L2 serve most of those reads.
+// Folded order of all three attention kernels.  Every workgroup of a head streams that head's K/V
+// rows (forward, dQ) or Q/dO rows (dK/dV), and a tile's sweep is as long as its distance from the
+// end of the causal triangle.  A workgroup works a PAIR of tiles of one head, the p-th longest and
+// the p-th shortest, so every workgroup of a launch has the same length (ntiles + 1 tile units): a
+// launch is a whole number of equal rounds and no compute unit waits for a straggler, whatever S
+// is.  Chunks of kChunk consecutive pairs go to one XCD (the dispatcher deals consecutive workgroup
+// ids round-robin to the 8 XCDs; an XCD has 32 compute units and these kernels run one workgroup
+// per unit), chunks of one head to the 8 XCDs of a round.  The long tile is swept from the end all
+// tiles share towards its own end, the short tile the other way round (forward and dQ: keys upwards
+// from row 0, then downwards to row 0; dK/dV: queries downwards from row S-1, then upwards to it).
+// Workgroup s of a chunk ends its first sweep a fixed number of steps per s before workgroup 0 and
+// begins its second one as many steps further from the shared end, so the lengths cancel and the
+// workgroups of an XCD read the same rows at about the same time in both sweeps, which is what
+// lets that XCD's L2 serve most of those reads (measured: 32 workgroups, one fetch from the fabric,
+// up to S = 256K; at S = 1M the forward keeps that, the two backward kernels drift apart over their
+// 16384 steps and fetch about half of what they stream).
 struct PairId { int64_t first, second; int h, b; };   // first < 0: nothing to do; second < 0: one tile only
 
 __host__ __device__ inline int64_t folded_grid(int64_t ntiles, int64_t heads)

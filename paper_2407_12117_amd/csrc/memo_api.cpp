@@ -28,11 +28,10 @@ memo_status check_desc(const memo_attn_desc *d, memo::AttnArgs *out)
     if (d->stride_b % vec || d->stride_s % vec || d->stride_h % vec) return MEMO_ERR_UNSUPPORTED;
     // the tile index arithmetic is 64-bit; the row count per launch must fit the grid
     if (d->S > ((int64_t)1 << 31) - 1024) return MEMO_ERR_UNSUPPORTED;
-    // one workgroup per 256-key tile in the dK/dV kernel; the forward and dQ kernels launch one per
-    // pair of 256-query tiles, in chunks of 32 pairs per head rounded up to a multiple of 8 chunks
+    // every bf16 kernel launches one workgroup per pair of 256-row tiles, in chunks of 32 pairs per head
+    // rounded up to a multiple of 8 chunks
     if (d->dtype == MEMO_BF16) {
         const int64_t hb = (int64_t)d->H * d->B;
-        if ((d->S + 255) / 256 * hb > 0x7fffffffLL) return MEMO_ERR_UNSUPPORTED;
         if (((((d->S + 255) / 256 + 1) / 2 + 31) / 32 * hb + 7) / 8 * 256 > 0x7fffffffLL) return MEMO_ERR_UNSUPPORTED;
     }
     // the bf16 tile fills address 64 rows with 32-bit per-lane byte offsets

@@ -214,7 +214,7 @@ static void attention_front_end()
           MEMO_ERR_INVALID_ARG);
     d.S = (int64_t)1 << 31;
     CHECK(memo_attn_fwd(&d, p, p, p, p, reinterpret_cast<float *>(p), nullptr) == MEMO_ERR_UNSUPPORTED);
-    d.S = (int64_t)1 << 30, d.H = 512;
+    d.S = (int64_t)1 << 30, d.H = 1024;
     CHECK(memo_attn_fwd(&d, p, p, p, p, reinterpret_cast<float *>(p), nullptr) == MEMO_ERR_UNSUPPORTED);
     CHECK(fake::launches == before + 2);
     CHECK(memo_layernorm_rows(p, p, p, p, 10, 512, 1e-5f, 3, 10, nullptr) == MEMO_OK);

@@ -83,8 +83,8 @@ def _desc(**kw):
     (dict(stride_s=132), mb.MEMO_ERR_UNSUPPORTED),    # rows not 16-byte aligned
     (dict(stride_s=64), mb.MEMO_ERR_INVALID_ARG),     # rows overlap
     (dict(stride_s=(1 << 24) + 8, stride_b=1 << 40), mb.MEMO_ERR_UNSUPPORTED),   # 64 rows span over 4 GiB
-    # one workgroup per 256-key tile: 2^22 tiles x 512 heads does not fit a grid
-    (dict(S=1 << 30, H=512, stride_s=512 * 128, stride_b=1 << 50), mb.MEMO_ERR_UNSUPPORTED),
+    # one workgroup per pair of 256-row tiles: 2^21 pairs x 1024 heads does not fit a grid
+    (dict(S=1 << 30, H=1024, stride_s=1024 * 128, stride_b=1 << 50), mb.MEMO_ERR_UNSUPPORTED),
 ])
 def test_attention_rejects_bad_descriptors_before_any_launch(kw, status):
     d = _desc(**kw)
