@@ -39,6 +39,9 @@ namespace {
 // share a K/V tile, the less fill traffic (L2 -> LDS) each MFMA has to pay for.
 constexpr int kFwdWaves = 8;                 // waves per workgroup
 constexpr int kFwdBq = 32 * kFwdWaves, kBk = 64;
+// A lane's 32 exponentials of a tile may sum to this much before the running maximum is brought up to
+// date: 2^40 per tile leaves the row sum over 2^20 keys and the output accumulators far inside fp32.
+constexpr float kRescaleAbove = 1099511627776.f;
 
 __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs a)
 {
@@ -140,18 +143,42 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
                 for (int e = 0; e < 16; ++e)
                     if (32 * jb + 8 * (e >> 2) + (e & 3) > thr) s[jb][e] = -INFINITY;
         }
-        // 32 values in 16 three-input maxima (two chains)
-        float mt = fmaxf(fmaxf(s[0][0], s[0][1]), s[0][2]), mu = fmaxf(fmaxf(s[1][0], s[1][1]), s[1][2]);
+        // P^T = exp2(c S^T - c m) against the running maximum m AS IT STANDS, rounded to bf16 for the second
+        // contraction, and its row sums.  Softmax does not need the true maximum, only one that keeps the
+        // exponentials in range: O and the logsumexp come out of (accO, lsum, m) the same whatever m is, and
+        // fp32 and bf16 keep their relative precision at any exponent.  So the maximum of the tile is not
+        // formed at all (16 three-input maxima, an exchange between the half-waves, and the exponentials
+        // waiting for both) unless some row sum shows a score far above m, which also covers the first
+        // tile, where m = -inf gives +inf or NaN here.
+        bf16x8 pB[4];
+        float psum0, psum1;
+        auto exponentials = [&]() __attribute__((always_inline)) {
+            psum0 = psum1 = 0.f;
 #pragma unroll
-        for (int e = 3; e < 15; e += 2) {
-            mt = fmaxf(fmaxf(mt, s[0][e]), s[0][e + 1]);
-            mu = fmaxf(fmaxf(mu, s[1][e]), s[1][e + 1]);
-        }
-        mt = fmaxf(fmaxf(mt, s[0][15]), fmaxf(mu, s[1][15]));
-        mt = max_across_halves(mt);
-        // Rescale only when some row of the wave sees a new maximum (rare after the first tiles).
-        // Every processed tile has key j0 visible to all 32 rows, so the maximum is finite.
-        if (__builtin_amdgcn_ballot_w64(mt > m) != 0) {
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int e = 0; e < 16; e += 2) {
+                    const f32x2 two = {__builtin_amdgcn_exp2f(fmaf(s[jb][e], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s[jb][e + 1], c, -mc))};
+                    psum0 += two[0];
+                    psum1 += two[1];
+                    const bf16x2 r = __builtin_convertvector(two, bf16x2);
+                    pB[2 * jb + (e >> 3)][e & 7] = r[0];
+                    pB[2 * jb + (e >> 3)][(e & 7) + 1] = r[1];
+                }
+        };
+        exponentials();
+        // not (sum <= bound) rather than sum > bound: a NaN sum takes the careful path too
+        if (__builtin_amdgcn_ballot_w64(!(psum0 + psum1 <= kRescaleAbove)) != 0) {
+            // 32 values in 16 three-input maxima (two chains)
+            float mt = fmaxf(fmaxf(s[0][0], s[0][1]), s[0][2]), mu = fmaxf(fmaxf(s[1][0], s[1][1]), s[1][2]);
+#pragma unroll
+            for (int e = 3; e < 15; e += 2) {
+                mt = fmaxf(fmaxf(mt, s[0][e]), s[0][e + 1]);
+                mu = fmaxf(fmaxf(mu, s[1][e]), s[1][e + 1]);
+            }
+            mt = fmaxf(fmaxf(mt, s[0][15]), fmaxf(mu, s[1][15]));
+            mt = max_across_halves(mt);
+            // Every processed tile has key j0 visible to all 32 rows, so the maximum is finite.
             const float m_new = fmaxf(m, mt);
             const float corr = __builtin_amdgcn_exp2f((m - m_new) * c);
             m = m_new;
@@ -161,22 +188,12 @@ __global__ __launch_bounds__(64 * kFwdWaves) void attn_fwd_bf16_kernel(AttnArgs 
             for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) accO[cb][e] *= corr;
-        }
-        float psum0 = 0.f, psum1 = 0.f;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            s[0][e] = __builtin_amdgcn_exp2f(fmaf(s[0][e], c, -mc));
-            s[1][e] = __builtin_amdgcn_exp2f(fmaf(s[1][e], c, -mc));
-            psum0 += s[0][e];
-            psum1 += s[1][e];
+            exponentials();
         }
         lsum += psum0 + psum1;
 
         // O^T += V^T P^T : A = V^T (transposed LDS read), B = P^T straight from the score registers.
         // item n = (kj = n/4, cb = n%4)
-        bf16x8 pB[4];
-#pragma unroll
-        for (int kj = 0; kj < 4; ++kj) pB[kj] = pack8(s[kj >> 1], 8 * (kj & 1));
         lds_pipeline_body<16, 2, 2>(vring, v_issue, [&](auto n, TrSlot &slot) {
             constexpr int kj = decltype(n)::value / 4, cb = decltype(n)::value % 4;
             accO[cb] = mfma32(tr_operand(slot), pB[kj], accO[cb]);

@@ -67,6 +67,28 @@ def test_bf16_scale_above_the_usual_one(oracle):
     _dense_case(oracle, 1, 500, 2, 128, "bf16", 41, scale=0.2, scaled=True)
 
 
+@pytest.mark.parametrize("log2_per_tile", [3.0, 12.0, 500.0])
+def test_bf16_forward_with_scores_climbing_along_the_keys(oracle, log2_per_tile):
+    # The forward keeps a running maximum that it brings up to date only when a row sum shows a score
+    # far above it (2^40).  Here every score grows with the key index by `log2_per_tile` binary orders
+    # of magnitude per 64-key tile: 3 and 12 let the exponentials run up to 2^40 between updates, 500
+    # forces an update (and the rescaling of everything accumulated so far) on every tile.
+    # Forward only: with a common offset this large in K, dQ and dK are differences of nearly equal
+    # sums, which the bf16 rounding of dS alone moves by several per cent in any implementation.
+    B, S, H, d = 1, 1100, 2, 128
+    scale = synth.default_scale(d)
+    q, k, v, _ = synth.attn_inputs(B, S, H, d, "bf16", 77)
+    slope = log2_per_tile / 64.0 / (scale * math.log2(math.e))        # growth of q.k per key
+    q = (0.05 * q.float() + 1.0).to(torch.bfloat16)                     # q.k = sum_c k_c, nearly
+    k = (0.05 * k.float() + (slope / d) * torch.arange(S, dtype=torch.float32).view(1, S, 1, 1)).to(torch.bfloat16)
+    print(f"[case] climbing scores, {log2_per_tile} binary orders per tile", flush=True)
+    o, lse = mb.memo_attn_fwd(q.cuda(), k.cuda(), v.cuda(), scale)
+    ro, rlse = oracle.attn_fwd(to_f64(q), to_f64(k), to_f64(v), scale)
+    assert_close("O", to_f64(o), ro, "bf16")
+    # the logsumexp itself grows to thousands here: fp32 holds it to a relative 2^-24 or so
+    assert np.abs(to_f64(lse) - rlse).max() <= LSE_MAX_ABS_BF16 * max(1.0, np.abs(rlse).max())
+
+
 def test_bf16_nan_in_one_key_row_reaches_what_depends_on_it():
     # a NaN in key row j of head 0: o, lse, dq of query rows i >= j are non-finite (they see the key),
     # rows before the 256-row block of j are bit-identical to the clean run (inside the block a masked
