@@ -30,11 +30,11 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # figures are carried here per workload; a workload that was not profiled reports null.
 GIB = float(1 << 30)
 TRAFFIC_SOURCE = ("carried from profiles/attn_c5_counters.md (two rocprofv3 --pmc runs of this command), not read "
-                  "in this run; it varies by about +-25 % between runs with the timing of the workgroups")
+                  "in this run; it varies by tens of per cent between runs with the timing of the workgroups (how long the 32 workgroups of an XCD stay in step)")
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "C5": {"attn_fwd_bf16_kernel": (404.1 + 1.02) * GIB,
-           "attn_bwd_dkdv_bf16_kernel": (724.8 + 2.00) * GIB,
-           "attn_bwd_dq_bf16_kernel": (631.7 + 1.00) * GIB},
+    "C5": {"attn_fwd_bf16_kernel": (1210.9 + 1.02) * GIB,
+           "attn_bwd_dkdv_bf16_kernel": (1253.5 + 2.00) * GIB,
+           "attn_bwd_dq_bf16_kernel": (2136.5 + 1.00) * GIB},
 }
 
 
@@ -96,7 +96,8 @@ def parity_check(torch, mb, synth, cfg, q, k, v, g, o, lse, dq, dk, dv, scale, n
     return out
 
 
-def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, calibrate_copy=False, parity=True):
+def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, calibrate_copy=False, parity=True,
+                 swap=True):
     """One workload: parity check, timed steps, per-kernel events, overlap section, CPU baseline.
     Returns the JSON object."""
     cfg = synth.CONFIGS[name]
@@ -127,17 +128,20 @@ def run_workload(torch, mb, synth, name, steps, warmup, overlap=True, cpu=True, 
         f0, f1 = ev(), ev()
         stages = [ev() for _ in range(4)]
         produced.record(compute)
-        mb.memo_swap_out(act, alpha, host, offload, wait_event=produced, done_event=offloaded)
+        if swap:
+            mb.memo_swap_out(act, alpha, host, offload, wait_event=produced, done_event=offloaded)
         f0.record(compute)
         mb.memo_attn_fwd(q, k, v, scale, o=o, lse=lse)
         f1.record(compute)
         # backward of the layer: prefetch the swapped tokens while attention backward runs (the
         # copy starts once the tokens are on the host AND the forward has ended, as in the
         # schedule of Section 4.1 where a layer's swap-in runs beside a later layer's backward)
-        prefetch.wait_event(f1)
-        mb.memo_swap_in(act_back, alpha, host, prefetch, wait_event=offloaded, done_event=fetched)
+        if swap:
+            prefetch.wait_event(f1)
+            mb.memo_swap_in(act_back, alpha, host, prefetch, wait_event=offloaded, done_event=fetched)
         mb.memo_attn_bwd(q, k, v, o, lse, g, scale, dq=dq, dk=dk, dv=dv, workspace=ws, stage_events=stages)
-        compute.wait_event(fetched)                      # the consumer of the activation waits here
+        if swap:
+            compute.wait_event(fetched)                  # the consumer of the activation waits here
         if rec is not None:
             rec.setdefault("fwd", []).append((f0, f1))
             rec.setdefault("stages", []).append(stages)
@@ -291,6 +295,9 @@ def main():
                     help="skip the additional S=256K workload that the default run also times")
     ap.add_argument("--no-overlap", action="store_true",
                     help="skip the separate swap/compute overlap measurement (profiling runs)")
+    ap.add_argument("--no-swap", action="store_true",
+                    help="attention kernels only, no swap-out/swap-in beside them (counter runs of the kernels alone; "
+                         "the line then is not the benchmark's step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy kernel (reference for HBM counters)")
     ap.add_argument("--schedule", default=None, metavar="S[,S...]",
@@ -328,7 +335,10 @@ def main():
         atomic_probe(torch)
         return
     out = run_workload(torch, mb, synth, args.config, args.steps, args.warmup, overlap=not args.no_overlap,
-                       cpu=not args.no_cpu_baseline, calibrate_copy=args.calibrate_copy)
+                       cpu=not args.no_cpu_baseline, calibrate_copy=args.calibrate_copy, swap=not args.no_swap)
+    if args.no_swap:
+        out["note"] = "--no-swap: attention kernels only; not the benchmark's step"
+        out["swap"] = None
     if args.config == "C5" and not args.no_extra:
         # the metric names S = 256K beside 1M: the 13B-shaped 256K workload and the two shorter ones,
         # timed the same way (no overlap section, no CPU leg), ride along in the same line
@@ -356,9 +366,11 @@ def bench_aids():
 
 
 def atomic_probe(torch):
-    """What a fused five-contraction backward would pay for dQ: a key-stationary workgroup (128 keys) has a
-    64 x 128 fp32 partial dQ (32 KB) to add to global memory per query tile step.  Measures the chip's rate
-    for exactly that pattern and prices the atomics alone at C3 and C5 against the dQ kernel they would replace."""
+    """What a fused five-contraction backward would pay for dQ: a key-stationary workgroup (256 keys) has a
+    32 x 128 fp32 partial dQ (16 KB) to add to global memory per query tile step, after a reduction over its
+    eight key-block waves through LDS (eight times that without).  Measures the chip's rate for that pattern
+    (32 KB blocks, workgroups of one head walking forward a few blocks apart) and prices the atomics alone at
+    C3 and C5 against the dQ kernel they would replace."""
     import ctypes
     aids = bench_aids()
     aids.memo_bench_atomic_add.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -384,10 +396,10 @@ def atomic_probe(torch):
     rate = max(r["TB_per_s"] for r in rows if r["op"] == "device-scope atomic add") * 1e12
     cost = {}
     for name, S, H in (("C3", 131072, 4), ("C5", 1048576, 4)):
-        steps = (S / 128.0) * (S / 64.0) / 2.0 * H       # visible (key tile, query tile) pairs
-        cost[name] = {"atomic_bytes_after_lds_reduction": steps * 32768.0,
-                      "atomics_alone_ms": steps * 32768.0 / rate * 1e3,
-                      "atomics_alone_unreduced_ms": steps * 4 * 32768.0 / rate * 1e3}
+        steps = (S / 256.0) * (S / 32.0) / 2.0 * H       # visible (key tile, query tile) pairs
+        cost[name] = {"atomic_bytes_after_lds_reduction": steps * 16384.0,
+                      "atomics_alone_ms": steps * 16384.0 / rate * 1e3,
+                      "atomics_alone_unreduced_ms": steps * 8 * 16384.0 / rate * 1e3}
     print(json.dumps({"metric": "fp32 atomic-add rate in the dQ pattern of a fused backward", "unit": "TB/s of operand bytes",
                       "rows": rows, "fused_backward_dq_cost": cost}), flush=True)
 

@@ -1,8 +1,10 @@
 // Benchmark aid (not part of libmemo): the rate at which the chip retires fp32 atomic adds in the
 // access pattern a fused five-contraction backward would produce for dQ.  In such a kernel the
-// key-stationary workgroup (128 keys) adds a 64 x 128 fp32 partial dQ (32 KB) to global memory per
-// query tile step; `dup` = 4 models the four key-block waves adding unreduced partials, `dup` = 1 a
-// reduction through LDS first.  Workgroup w of head w % heads starts at row block 2 * (w / heads)
+// key-stationary workgroup adds an fp32 partial dQ of its query tile to global memory per step: blocks
+// of 32 KB here (64 queries x 128, the tile of a 128-key workgroup; the 256-key workgroup of the
+// library would add 16 KB per 32-query step, which only changes how many such blocks there are).
+// `dup` = 4 models several key-block waves adding unreduced partials, `dup` = 1 a reduction through
+// LDS first.  Workgroup w of head w % heads starts at row block 2 * (w / heads)
 // and walks forward, as the key tiles of one head do.  scope: 0 device-scope atomics, 1 workgroup-
 // scope atomics, 2 plain stores of the same bytes (for reference).
 #include <hip/hip_runtime.h>
