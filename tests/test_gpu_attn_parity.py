@@ -52,7 +52,7 @@ def test_bf16_multi_tile(oracle, B, S, H):
 
 
 def test_bf16_many_query_tiles_dense(oracle):
-    # every element of dK, dV compared where the dK/dV kernel's query loop runs up to 258 times
+    # every element of dK, dV compared where the dK/dV kernel's query loop runs up to 515 times
     # (key tile 0) and the forward / dQ kernels walk up to 258 key tiles; ragged tail
     _dense_case(oracle, 1, 16461, 1, 128, "bf16", 333)
 

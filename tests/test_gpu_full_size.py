@@ -22,7 +22,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _sample_rows(S, rng):
-    fixed = [0, 1, 31, 32, 63, 64, 127, 128, 129, S // 2 - 1, S // 2, S - 129, S - 128, S - 2, S - 1]
+    fixed = [0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256, 257, S // 2 - 1, S // 2, S - 257, S - 256, S - 129, S - 128, S - 2, S - 1]
     rand = rng.integers(0, S, size=9).tolist()
     return np.array(sorted(set(r for r in fixed + rand if 0 <= r < S)), dtype=np.int64)
 
