@@ -63,9 +63,12 @@ def cpu_baseline(cfg, q, k, v, g, scale, budget_s=15.0):
     n = int(max(threads, min(4096, len(rows) * budget_s / max(dt, 1e-3))))
     rows = rows_for(n)
     dt, fl = run(rows)
+    # the dense oracle forms every product once more for dK/dV: 7 contractions per visible pair over all heads
+    dense_flop = 7.0 * float(S) * float(S) * d * cfg["H"] * cfg["B"]
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
             "sample": f"fp64 oracle forward+dQ of {len(rows)} uniformly spaced query rows of head 0 "
-                      f"at S={S}, d={d} ({fl / 1e9:.1f} GFLOP in {dt:.1f} s)"}
+                      f"at S={S}, d={d} ({fl / 1e9:.1f} GFLOP in {dt:.1f} s)",
+            "dense_oracle_hours_extrapolated": dense_flop / (fl / dt) / 3600.0}
 
 
 def parity_check(torch, mb, synth, cfg, q, k, v, g, o, lse, dq, dk, dv, scale, n_rows=12, tail=32):
