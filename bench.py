@@ -63,8 +63,9 @@ def cpu_baseline(cfg, q, k, v, g, scale, budget_s=15.0):
     n = int(max(threads, min(4096, len(rows) * budget_s / max(dt, 1e-3))))
     rows = rows_for(n)
     dt, fl = run(rows)
-    # the dense oracle forms every product once more for dK/dV: 7 contractions per visible pair over all heads
-    dense_flop = 7.0 * float(S) * float(S) * d * cfg["H"] * cfg["B"]
+    # the dense oracle takes these 4 contractions per visible pair row by row and 4 more column by column
+    # for dK and dV (it shares nothing between the two), over all heads
+    dense_flop = 8.0 * float(S) * float(S) * d * cfg["H"] * cfg["B"]
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
             "sample": f"fp64 oracle forward+dQ of {len(rows)} uniformly spaced query rows of head 0 "
                       f"at S={S}, d={d} ({fl / 1e9:.1f} GFLOP in {dt:.1f} s)",
