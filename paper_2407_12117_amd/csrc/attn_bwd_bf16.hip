@@ -5,8 +5,9 @@
 // dQ = scale dS K, D_i = dO_i . O_i.  Two kernels: a key-stationary one for dK, dV and a
 // query-stationary one for dQ; no atomics, so the gradients are bit-reproducible.  S and dP are
 // formed in both (7 contractions for the method's 5): the alternative, one kernel that adds its dQ
-// partials to global memory, needs 32 KB of fp32 atomic adds per 64 x 128 tile step, and this chip
-// retires those at 1.4 TB/s, several times slower than the dQ kernel they would replace.
+// partials to global memory, needs 16 KB of fp32 atomic adds per 32-query step of a 256-key
+// workgroup, and this chip retires those at 1.4 TB/s: 2.5 times slower than the dQ kernel they
+// would replace.
 //
 // Why this MFMA shape: the chip is power-limited on random data and the 16x16x32 instruction
 // spends less energy per flop than the 32x32x16 one (an MFMA-only loop sustains about an eighth
@@ -23,8 +24,9 @@
 // to bf16, are directly the B operand of the next contraction: two D blocks stacked along the
 // rows give a lane the 8 contraction slots  e <-> row 16*(e/4) + 4*g4 + e%4  of a 32-row chunk,
 // and the matching A operand is two transposed LDS reads (ds_read_b64_tr_b16) of rows
-// 4*g4 .. 4*g4+3 and 16 + 4*g4 .. of that chunk.  LDS tiles are 64 rows x 256 bytes with the
-// SwzB chunk swizzle (bf16_tiles.h); all operand reads are issued by hand ahead of their MFMAs.
+// 4*g4 .. 4*g4+3 and 16 + 4*g4 .. of that chunk.  LDS tiles are rows of 256 bytes (64 per K/V tile
+// of the dQ kernel, 32 per Q/dO tile of the dK/dV kernel) with the SwzB chunk swizzle
+// (bf16_tiles.h); all operand reads are issued by hand ahead of their MFMAs.
 #include "bf16_tiles.h"
 
 namespace memo {
