@@ -138,6 +138,39 @@ def test_bf16_strided_views_of_a_packed_qkv(oracle):
     assert out[:, :, 1:].abs().max().item() == 0.0
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_bf16_random_shapes_and_row_padding(oracle, seed):
+    # shapes drawn at random (batch 1..2, heads 1..3, lengths on no tile edge in particular), rows
+    # of 128 values inside rows of 128, 136 or 192: all eight tensors share the padded layout
+    rng = np.random.default_rng(seed)
+    scale = synth.default_scale(128)
+    for case in range(5):
+        B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        S = int(rng.choice([rng.integers(1, 70), rng.integers(70, 600), rng.integers(600, 2200)]))
+        pad = int(rng.choice([0, 8, 64]))
+        print(f"[case] random shape seed={seed} B={B} S={S} H={H} pad={pad}", flush=True)
+
+        def padded(values=None):
+            buf = torch.zeros(B, S, H, 128 + pad, dtype=torch.bfloat16, device="cuda")[..., :128]
+            if values is not None:
+                buf.copy_(values)
+            return buf
+
+        q, k, v, g = synth.attn_inputs(B, S, H, 128, "bf16", 5000 + 10 * seed + case)
+        qd, kd, vd, gd = (padded(x) for x in (q, k, v, g))
+        o, lse = mb.memo_attn_fwd(qd, kd, vd, scale, o=padded())
+        dq, dk, dv = mb.memo_attn_bwd(qd, kd, vd, o, lse, gd, scale, dq=padded(), dk=padded(), dv=padded())
+        torch.cuda.synchronize()
+        qf, kf, vf, gf = (to_f64(x) for x in (q, k, v, g))
+        ro, rlse = oracle.attn_fwd(qf, kf, vf, scale)
+        rdq, rdk, rdv = oracle.attn_bwd(qf, kf, vf, gf, scale)
+        assert_close("O", to_f64(o), ro, "bf16")
+        assert np.abs(to_f64(lse) - rlse).max() <= LSE_MAX_ABS_BF16
+        assert_close("dQ", to_f64(dq), rdq, "bf16")
+        assert_close("dK", to_f64(dk), rdk, "bf16")
+        assert_close("dV", to_f64(dv), rdv, "bf16")
+
+
 def test_bf16_constant_values_give_constant_output():
     # rows of the softmax sum to one: V = 1 -> O = 1 (bf16 rounding of P allows 2^-8)
     B, S, H, d = 1, 1500, 2, 128
