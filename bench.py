@@ -526,8 +526,20 @@ def recompute_bench(torch, mb, args):
                          "layernorm_GBps": ln_bytes / (t_ln * 1e-3) / 1e9 if n else None,
                          "linear_TFLOPs": lin_flop / (t_lin * 1e-3) / 1e12 if n else None})
     full = rows_out[0] if rows_out and rows_out[0]["rows_recomputed"] == S else None
+    # context, not part of the path: the vendor library's GEMM of the same shape on the same data
+    lib_ms = 0.0
+    for r in range(args.warmup + max(1, args.steps)):
+        e0, e1 = ev(), ev()
+        e0.record()
+        torch.matmul(norm, w.t(), out=qkv)
+        e1.record()
+        torch.cuda.synchronize()
+        if r >= args.warmup:
+            lib_ms += e0.elapsed_time(e1) / max(1, args.steps)
     out = {"metric": "token-wise recomputation of input_norm and q,k,v", "unit": "ms", "S": S, "h": h, "N": N,
            "rows": rows_out,
+           "library_gemm_all_rows": {"what": "torch.matmul (hipBLASLt), no bias, same operands", "ms": lib_ms,
+                                     "TFLOPs": 2.0 * S * h * N / (lib_ms * 1e-3) / 1e12},
            "roofline_layernorm": None if not full else {"bound": "hbm", "achieved": full["layernorm_GBps"], "peak": 8000.0,
                                                         "unit": "GB/s", "frac": full["layernorm_GBps"] / 8000.0},
            "roofline_linear": None if not full else {"bound": "mfma", "achieved": full["linear_TFLOPs"],
